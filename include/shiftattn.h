@@ -1,0 +1,138 @@
+/*
+ * shiftattn — C ABI of the Shift Parallelism attention hot path on one MI355X (gfx950).
+ *
+ * The operation is causal grouped-query attention over ONE GPU's head shard, reading a
+ * paged KV cache whose layout is the same in the sequence-parallel (Ulysses) prefill mode
+ * and the tensor-parallel decode mode.  Source: the paper's section "Introducing Shift
+ * Parallelism" — the KV-cache layout does not change between SP and TP as long as
+ * SP x TP = P, and in both modes each GPU computes the same subset of attention heads over
+ * all tokens (Figure 2).  That invariance is structural here: sp_kv_append,
+ * sp_attn_prefill and sp_attn_decode take the same sp_cache_desc and block table, and the
+ * ABI has no re-layout entry point.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HBM) unless the name starts with host_.
+ *     The sp_cache_desc struct itself is read on the HOST at call time.
+ *   - bf16 tensors are raw 16-bit patterns; index arrays are int32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: no allocation, no synchronisation, no host<->device copies.
+ *   - The caller owns every buffer; the library keeps no device state between calls.
+ *   - Return value: SP_OK (0) or a negative sp_status.  On any error nothing is launched.
+ *     No exception crosses the ABI.  Device-side metadata (lengths, block-table entries)
+ *     is NOT validated by the three hot calls; sp_debug_validate_metadata does that,
+ *     synchronously, for tests.
+ *   - Page indexing (exact int32 arithmetic): token j of sequence s lives in physical page
+ *     block_table[s * max_pages_per_seq + j / 16], row j % 16.
+ *   - GQA map: query head h reads KV head h / (num_q_heads / num_kv_heads).
+ *   - Causal convention with a cached prefix: the query at absolute position p sees keys
+ *     0..p inclusive.
+ */
+#ifndef SHIFTATTN_H
+#define SHIFTATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sp_status {
+  SP_OK = 0,
+  SP_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  SP_ERR_BAD_SHAPE = -2,   /* negative count, num_q_heads % num_kv_heads != 0, ...          */
+  SP_ERR_UNSUPPORTED = -3, /* page_size != 16, head_dim not in {64,128}, causal != 1, ...   */
+  SP_ERR_WORKSPACE = -4,   /* workspace missing or too small                                */
+  SP_ERR_HIP = -5          /* HIP runtime error at launch; text in sp_last_error()          */
+} sp_status;
+
+/* The paged KV cache of one GPU's head shard.  Caller-owned device memory; the library
+ * never allocates, frees or re-lays it out.  Both pools have the layout
+ *     bf16 [num_pages][num_kv_heads][page_size = 16][head_dim]
+ * so every (page, kv head) is one contiguous 16 x head_dim block (4 KiB at head_dim 128). */
+typedef struct sp_cache_desc {
+  void *k_pages;        /* device, bf16                                                   */
+  void *v_pages;        /* device, bf16, same shape                                       */
+  int32_t num_pages;    /* physical pages in the pool                                     */
+  int32_t page_size;    /* must be 16                                                     */
+  int32_t num_kv_heads; /* KV heads of THIS shard (1 for Llama-3.3-70B at P = 8)          */
+  int32_t head_dim;     /* 64 or 128                                                      */
+} sp_cache_desc;
+
+/*
+ * sp_kv_append — write the new tokens' K and V into their pages (the step in front of both
+ * attention calls; it is what keeps one cache image valid for both modes).
+ *   k_new, v_new    bf16 [total_new_tokens][num_kv_heads][head_dim], packed by sequence
+ *   cu_seqlens_new  int32 [batch + 1] prefix sums of new tokens per sequence
+ *   ctx_lens        int32 [batch] tokens already cached per sequence; new token i of
+ *                   sequence s goes to absolute position ctx_lens[s] + i
+ *   block_table     int32 [batch][max_pages_per_seq]
+ * Sequences with zero new tokens are no-ops.  batch == 0 or total_new_tokens == 0 returns
+ * SP_OK without launching.  Slots not named by the inputs are left untouched.
+ */
+int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_new,
+                 const int32_t *cu_seqlens_new, const int32_t *ctx_lens,
+                 const int32_t *block_table, int32_t batch, int32_t max_pages_per_seq,
+                 int32_t total_new_tokens, void *stream);
+
+/*
+ * sp_attn_prefill — causal GQA attention for a packed varlen batch of query chunks (the SP
+ * mode after the sequence->head all-to-all, and chunked prefill against a cached prefix).
+ *   q, out          bf16 [total_q_tokens][num_q_heads][head_dim]; out is written with one
+ *                   round-to-nearest-even from fp32
+ *   cu_seqlens_q    int32 [batch + 1]
+ *   ctx_lens        int32 [batch] tokens cached BEFORE this chunk; the chunk's own K/V must
+ *                   already have been appended (query i of sequence s is at ctx_lens[s] + i)
+ *   max_q_len       host hint: >= the longest chunk in the batch (sizes the grid)
+ *   max_kv_len      host hint: >= the largest ctx_lens[s] + chunk length (unused rows cost
+ *                   nothing; it only bounds loops)
+ *   scale           softmax scale, normally 1/sqrt(head_dim)
+ *   causal          must be 1
+ *   workspace       unused by the current kernels; may be NULL with workspace_bytes 0
+ * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax.
+ */
+int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
+                    const int32_t *cu_seqlens_q, const int32_t *ctx_lens,
+                    const int32_t *block_table, int32_t batch, int32_t max_pages_per_seq,
+                    int32_t total_q_tokens, int32_t max_q_len, int32_t max_kv_len,
+                    int32_t num_q_heads, float scale, int32_t causal, void *workspace,
+                    size_t workspace_bytes, void *stream);
+
+/*
+ * sp_attn_decode — one query token per sequence (the TP mode), split over the key range
+ * with a log-sum-exp combine pass.
+ *   q, out          bf16 [batch][num_q_heads][head_dim]
+ *   seq_lens        int32 [batch] INCLUDING the current token, whose K/V is already cached;
+ *                   a sequence with seq_lens[s] == 0 gets an all-zero output row
+ *   max_seq_len     host hint: >= max seq_lens[s] (sizes the split grid and the workspace)
+ *   workspace       device scratch of at least sp_attn_decode_workspace_size(...) bytes for
+ *                   the per-split partial results; contents need no initialisation
+ */
+int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out,
+                   const int32_t *seq_lens, const int32_t *block_table, int32_t batch,
+                   int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads,
+                   float scale, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace the two attention calls need for the given host-side shape. */
+size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens,
+                                      int32_t num_q_heads, int32_t head_dim);
+size_t sp_attn_decode_workspace_size(int32_t batch, int32_t max_seq_len, int32_t num_q_heads,
+                                     int32_t head_dim);
+
+/*
+ * sp_debug_validate_metadata — SYNCHRONOUS test helper: copies the int32 arrays to the host
+ * and checks 0 <= page < num_pages for every page a sequence uses and
+ * ceil(seq_lens[s] / 16) <= max_pages_per_seq.  Returns SP_OK or SP_ERR_BAD_SHAPE.
+ */
+int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_lens,
+                               const int32_t *block_table, int32_t batch,
+                               int32_t max_pages_per_seq);
+
+const char *sp_status_string(int status); /* static string                              */
+const char *sp_last_error(void);          /* thread-local detail of the last failure    */
+int sp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHIFTATTN_H */

@@ -1,0 +1,90 @@
+// Tile-level building blocks shared by the prefill and decode attention kernels (gfx950).
+//
+// Orientation.  Scores are computed TRANSPOSED, S^T[kv][q] = K Q^T, with
+// v_mfma_f32_32x32x16_bf16: K rows are the M side (A operand), query columns the N side
+// (B operand).  A lane then owns ONE query column (lane & 31) and 16 key rows per 32-key
+// block, so the softmax reductions over keys are in-register plus one exchange between the
+// two wave halves.  The output is accumulated transposed as well, O^T[d][q] = V^T P^T:
+// the fp32 score accumulator of a lane, packed to bf16, is directly the B operand of that
+// second MFMA — P never goes through LDS.  The contraction index of the second MFMA (the key
+// index) may be permuted freely as long as both operands agree; the V^T operand is fetched
+// from the row-major V tile in LDS with ds_read_b64_tr_b16 in the row order the score
+// accumulator dictates.
+//
+// MFMA 32x32x16 register layouts (checked on hardware):
+//   A (32 x 16): lane l holds row l & 31, k = 8 * (l >> 5) + 0..7
+//   B (16 x 32): lane l holds col l & 31, k = 8 * (l >> 5) + 0..7
+//   C (32 x 32): lane l holds col l & 31, register r holds row 8 * (r / 4) + 4 * (l >> 5) + r % 4
+#pragma once
+#include "sp_common.h"
+
+namespace sp {
+
+template <int D>
+struct TileGeom {
+  static constexpr int kChunksPerRow = D / 8;   // 16-byte chunks in one K or V row
+  static constexpr int kKStride = D * 2 + 16;   // bytes; +16 spreads 16 consecutive rows over all banks
+  static constexpr int kVStride = D * 2 + 64;   // bytes; +64 makes 4 consecutive rows x 64 B bank-disjoint
+  static constexpr int kDSteps = D / 16;        // MFMA k-steps of the QK^T contraction
+  static constexpr int kDBlocks = D / 32;       // 32-row blocks of O^T
+};
+
+// LDS is addressed through explicit address-space-3 pointers so every access is a ds_* op.
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) float lds_float;
+
+__device__ __forceinline__ bf16x8 lds_read_k_operand(const lds_char *kbuf, int kstride, int row, int dchunk) {
+  return *(const lds_bf16x8 *)(kbuf + row * kstride + dchunk * 16);
+}
+
+// V^T operand for one (32-row d-block, 16-key step): two transposing 8-byte reads.
+// `vrow0` is the first of the 4 consecutive key rows this wave half supplies (the second
+// group of 4 sits 8 rows further), `dcol0` the first d column of the 32-wide block.
+__device__ __forceinline__ bf16x8 lds_read_vt_operand(const lds_char *vbuf, int vstride, int vrow0,
+                                                      int dcol0, int lane) {
+  int n = lane & 15, dg = (lane >> 4) & 1;
+  const lds_char *p = vbuf + (vrow0 + (n >> 2)) * vstride + (dcol0 + 16 * dg + 4 * (n & 3)) * 2;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * vstride));
+  union {
+    struct { s16x4 a, b; } s;
+    bf16x8 v;
+  } u;
+  u.s.a = lo;
+  u.s.b = hi;
+  return u.v;
+}
+
+// Exchange between the two 32-lane halves: returns the value held by lane ^ 32.
+__device__ __forceinline__ float other_half(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  // lower half: r[1] is the upper lane's value; upper half: r[0] is the lower lane's value
+  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &p, int r0) {
+  union {
+    bf16x2 h[4];
+    bf16x8 v;
+  } u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    u.h[i] = __builtin_convertvector((f32x2){p[r0 + 2 * i], p[r0 + 2 * i + 1]}, bf16x2);
+  return u.v;
+}
+
+// One 64-bit store of 4 consecutive bf16 outputs.
+__device__ __forceinline__ void store4_bf16(void *dst, float a, float b, float c, float d) {
+  union {
+    bf16x2 h[2];
+    u32x2 v;
+  } u;
+  u.h[0] = __builtin_convertvector((f32x2){a, b}, bf16x2);
+  u.h[1] = __builtin_convertvector((f32x2){c, d}, bf16x2);
+  *reinterpret_cast<u32x2 *>(dst) = u.v;
+}
+
+}  // namespace sp

@@ -1,0 +1,62 @@
+// KV append: scatter the new tokens' K and V rows into their 16-token pages.
+// This is the step that keeps ONE cache image valid for both the sequence-parallel prefill
+// and the tensor-parallel decode (the invariant KV layout of the paper's section
+// "Introducing Shift Parallelism").  Pure bit copy with exact int32 page indexing.
+//
+// Work decomposition: one lane moves one 16-byte chunk of K and the matching chunk of V.
+// A token row of one KV head (head_dim bf16) is head_dim/8 chunks, so at head_dim 128
+// sixteen adjacent lanes read and write one contiguous 256-byte row: fully coalesced on both
+// sides.  HBM-bound: 4 * head_dim bytes read + the same written per (token, kv head).
+#include "sp_common.h"
+
+namespace sp {
+
+__global__ __launch_bounds__(256) void kv_append_kernel(
+    u32x4 *__restrict__ k_pages, u32x4 *__restrict__ v_pages, const u32x4 *__restrict__ k_new,
+    const u32x4 *__restrict__ v_new, const int32_t *__restrict__ cu_new,
+    const int32_t *__restrict__ ctx_lens, const int32_t *__restrict__ block_table, int batch,
+    int max_pages, int num_pages, int chunks_per_head, int num_kv_heads, long total_chunks) {
+  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= total_chunks) return;
+  int chunks_per_token = chunks_per_head * num_kv_heads;
+  int tok = (int)(gid / chunks_per_token);
+  int rem = (int)(gid - (long)tok * chunks_per_token);
+  int g = rem / chunks_per_head;
+  int c = rem - g * chunks_per_head;
+
+  // Largest s with cu_new[s] <= tok (sequences with no new tokens are skipped over).
+  int lo = 0, hi = batch;
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (cu_new[mid] <= tok) lo = mid; else hi = mid;
+  }
+  int s = lo;
+  int pos = ctx_lens[s] + (tok - cu_new[s]);
+  int logical = pos >> 4;
+  if (pos < 0 || logical >= max_pages) return;
+  int page = block_table[(long)s * max_pages + logical];
+  if (page < 0 || page >= num_pages) return;  // bad metadata must not turn into a wild store
+  long dst = (((long)page * num_kv_heads + g) * kPage + (pos & 15)) * chunks_per_head + c;
+  u32x4 kv = __builtin_nontemporal_load(k_new + gid);
+  u32x4 vv = __builtin_nontemporal_load(v_new + gid);
+  k_pages[dst] = kv;
+  v_pages[dst] = vv;
+}
+
+int launch_kv_append(const sp_cache_desc &c, const void *k_new, const void *v_new,
+                     const int32_t *cu_new, const int32_t *ctx_lens, const int32_t *block_table,
+                     int batch, int max_pages, int total_new, hipStream_t stream) {
+  int chunks_per_head = c.head_dim / 8;
+  long total_chunks = (long)total_new * c.num_kv_heads * chunks_per_head;
+  long blocks = (total_chunks + 255) / 256;
+  if (blocks > 0x7fffffffL) return fail(SP_ERR_BAD_SHAPE, "sp_kv_append: too many tokens for one launch");
+  hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                     (u32x4 *)c.k_pages, (u32x4 *)c.v_pages, (const u32x4 *)k_new,
+                     (const u32x4 *)v_new, cu_new, ctx_lens, block_table, batch, max_pages,
+                     c.num_pages, chunks_per_head, c.num_kv_heads, total_chunks);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SP_ERR_HIP, "kv_append launch: %s", hipGetErrorString(e));
+  return SP_OK;
+}
+
+}  // namespace sp

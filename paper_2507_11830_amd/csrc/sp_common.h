@@ -1,0 +1,43 @@
+// Shared declarations for the gfx950 kernels of the Shift Parallelism attention hot path
+// (per-GPU head shard, paged KV cache with a mode-invariant layout; paper section
+// "Introducing Shift Parallelism").  Internal to the library: nothing here is part of the ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "shiftattn.h"
+
+namespace sp {
+
+constexpr int kPage = 16;  // tokens per KV page (fixed by the cache layout)
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// Records a failure text for sp_last_error() and passes the status through.
+int fail(int status, const char *fmt, ...);
+
+// Kernel launchers (each validates nothing: the entry points in api.hip did that).
+int launch_kv_append(const sp_cache_desc &c, const void *k_new, const void *v_new,
+                     const int32_t *cu_new, const int32_t *ctx_lens, const int32_t *block_table,
+                     int batch, int max_pages, int total_new, hipStream_t stream);
+
+int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
+                   const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
+                   int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
+                   hipStream_t stream);
+
+size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);
+int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
+                  const int32_t *block_table, int batch, int max_pages, int max_seq_len,
+                  int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
+                  hipStream_t stream);
+
+}  // namespace sp

@@ -1,0 +1,116 @@
+"""Test plumbing: run the same seeded Workload steps through the HIP library (via the Python
+binding of the C ABI) and through the fp64 oracle, and compare.  No arithmetic of the method
+lives here."""
+from __future__ import annotations
+
+import numpy as np
+
+import workloads as W
+
+TOL = 1e-2   # max abs error GPU(bf16 out) vs fp64 oracle; bf16 inputs, fp32 accumulation
+
+
+def to_dev(u16: np.ndarray):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def dev_i32(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def bits_of(t) -> np.ndarray:
+    import torch
+
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class GpuRunner:
+    """Owns the device cache of a workload and feeds steps to the library."""
+
+    def __init__(self, w: W.Workload):
+        import paper_2507_11830_amd as sp
+
+        self.sp, self.w = sp, w
+        self.cache = sp.KVCache.empty(w.num_pages, w.Hkv, w.d, fill_bits=W.CANARY)
+        self.bt = dev_i32(w.block_table)
+        self.ws = None
+
+    def append(self, st: W.Step):
+        self.sp.sp_kv_append(self.cache, to_dev(st.k_new), to_dev(st.v_new), dev_i32(st.cu_new),
+                             dev_i32(st.ctx_lens), self.bt)
+
+    def attend(self, st: W.Step):
+        import torch
+
+        w, sp = self.w, self.sp
+        q = to_dev(st.q)
+        out = torch.empty_like(q)
+        if st.kind == "prefill":
+            sp.sp_attn_prefill(self.cache, q, out, dev_i32(st.cu_new), dev_i32(st.ctx_lens), self.bt,
+                               int(st.new_lens.max()), int(st.seq_lens.max()), float(w.scale))
+        else:
+            seq_lens = st.seq_lens
+            mx = int(seq_lens.max())
+            need = sp.sp_attn_decode_workspace_size(w.batch, mx, w.Hq, w.d)
+            if self.ws is None or self.ws.numel() < need:
+                self.ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+            sp.sp_attn_decode(self.cache, q, out, dev_i32(seq_lens), self.bt, mx, float(w.scale), self.ws)
+        torch.cuda.synchronize()
+        return bits_of(out)
+
+    def cache_bits(self):
+        return bits_of(self.cache.k_pages), bits_of(self.cache.v_pages)
+
+
+class OracleRunner:
+    def __init__(self, w: W.Workload):
+        import oracle
+
+        self.o, self.w = oracle, w
+        self.kp, self.vp = w.empty_cache()
+
+    def append(self, st: W.Step):
+        self.o.kv_append(self.kp, self.vp, st.k_new, st.v_new, st.cu_new, st.ctx_lens, self.w.block_table)
+
+    def attend(self, st: W.Step) -> np.ndarray:
+        w = self.w
+        if st.kind == "prefill":
+            return self.o.attn_prefill(self.kp, self.vp, st.q, st.cu_new, st.ctx_lens, w.block_table, w.scale)
+        return self.o.attn_decode(self.kp, self.vp, st.q, st.seq_lens, w.block_table, w.scale)
+
+    def attend_rows(self, st: W.Step, row_seq, row_tok, row_head) -> np.ndarray:
+        w = self.w
+        return self.o.attn_prefill_rows(self.kp, self.vp, st.q, st.cu_new, st.ctx_lens, w.block_table,
+                                        w.scale, row_seq, row_tok, row_head)
+
+
+def report_err(name, got_bits, want):
+    got = W.bf16_bits_to_f64(got_bits)
+    err = np.abs(got - want)
+    assert np.isfinite(got).all(), f"{name}: non-finite GPU output"
+    idx = np.unravel_index(np.argmax(err), err.shape)
+    print(f"[parity] {name}: max abs err {err.max():.5f} at {idx} (gpu {got[idx]:.5f} oracle {want[idx]:.5f})",
+          flush=True)
+    return float(err.max())
+
+
+def sample_rows(rng, st: W.Step, Hq: int, n: int):
+    """n random (seq, token-in-chunk, head) triples, always including the first and last rows."""
+    lens = st.new_lens
+    seqs = np.nonzero(lens > 0)[0]
+    rs = rng.choice(seqs, size=n, p=lens[seqs] / lens[seqs].sum())
+    rt = np.array([rng.integers(0, lens[s]) for s in rs])
+    rh = rng.integers(0, Hq, size=n)
+    s_last = seqs[-1]
+    rs[:4] = [seqs[0], seqs[0], s_last, s_last]
+    rt[:4] = [0, min(1, lens[seqs[0]] - 1), lens[s_last] - 1, max(0, lens[s_last] - 2)]
+    return rs.astype(np.int32), rt.astype(np.int32), rh.astype(np.int32)
+
+
+def gather_rows(out_bits, st: W.Step, rs, rt, rh):
+    tok = st.cu_new[rs] + rt
+    return out_bits[tok, rh]

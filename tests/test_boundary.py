@@ -1,0 +1,92 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads, every symbol
+the header declares is exported, and the header and the Python binding agree."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def built_lib():
+    import paper_2507_11830_amd as sp
+    from paper_2507_11830_amd import build as b
+
+    if not os.path.exists(sp.LIB_PATH):
+        b.build()
+    return ctypes.CDLL(sp.LIB_PATH)
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "shiftattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sp_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_hot_calls():
+    names = header_functions()
+    for n in ("sp_kv_append", "sp_attn_prefill", "sp_attn_decode"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(built_lib):
+    for n in header_functions():
+        assert hasattr(built_lib, n), f"{n} declared in shiftattn.h but not exported"
+
+
+def test_binding_names_match_header():
+    import paper_2507_11830_amd as sp
+
+    assert sorted(sp.EXPORTS) == header_functions()
+    for n in ("sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_attn_decode_workspace_size"):
+        assert callable(getattr(sp, n))
+
+
+def test_status_strings_and_version(built_lib):
+    built_lib.sp_status_string.restype = ctypes.c_char_p
+    assert built_lib.sp_status_string(0) == b"SP_OK"
+    assert built_lib.sp_status_string(-4) == b"SP_ERR_WORKSPACE"
+    assert built_lib.sp_version() >= 100
+
+
+def test_workspace_size_is_host_only_arithmetic(built_lib):
+    f = built_lib.sp_attn_decode_workspace_size
+    f.restype = ctypes.c_size_t
+    f.argtypes = [ctypes.c_int32] * 4
+    assert f(0, 100, 8, 128) == 0 and f(4, 0, 8, 128) == 0
+    a, b = f(64, 8192, 8, 128), f(64, 16384, 8, 128)
+    assert 0 < a <= b
+    # at least one (o[d], m, l) fp32 partial per (sequence, head)
+    assert f(1, 1, 8, 128) >= 8 * 130 * 4
+
+
+def test_argument_validation_needs_no_gpu(built_lib):
+    """Validation happens before any HIP call, so these return codes are checkable on a CPU machine."""
+    import paper_2507_11830_amd as sp
+
+    L = sp.lib()
+    d = sp.sp_cache_desc(0x1000, 0x2000, 8, 16, 1, 128)
+    one = ctypes.c_void_p(0x4000)
+    assert L.sp_kv_append(None, one, one, one, one, one, 1, 1, 1, None) == sp.SP_ERR_NULL
+    assert L.sp_kv_append(ctypes.byref(d), one, one, one, one, one, 0, 1, 0, None) == sp.SP_OK
+    assert L.sp_kv_append(ctypes.byref(d), None, one, one, one, one, 1, 1, 1, None) == sp.SP_ERR_NULL
+    assert L.sp_kv_append(ctypes.byref(d), one, one, one, one, one, -1, 1, 1, None) == sp.SP_ERR_BAD_SHAPE
+    bad_page = sp.sp_cache_desc(0x1000, 0x2000, 8, 32, 1, 128)
+    assert L.sp_kv_append(ctypes.byref(bad_page), one, one, one, one, one, 1, 1, 1, None) == sp.SP_ERR_UNSUPPORTED
+    bad_dim = sp.sp_cache_desc(0x1000, 0x2000, 8, 16, 1, 96)
+    assert L.sp_attn_decode(ctypes.byref(bad_dim), one, one, one, one, 1, 1, 16, 8, 0.1, one, 1 << 20, None) == sp.SP_ERR_UNSUPPORTED
+    # Hq not a multiple of Hkv
+    d3 = sp.sp_cache_desc(0x1000, 0x2000, 8, 16, 3, 128)
+    assert L.sp_attn_decode(ctypes.byref(d3), one, one, one, one, 1, 1, 16, 8, 0.1, one, 1 << 20, None) == sp.SP_ERR_BAD_SHAPE
+    # non-causal, bad scale
+    assert L.sp_attn_prefill(ctypes.byref(d), one, one, one, one, one, 1, 1, 4, 4, 4, 8, 0.1, 0, None, 0, None) == sp.SP_ERR_UNSUPPORTED
+    assert L.sp_attn_prefill(ctypes.byref(d), one, one, one, one, one, 1, 1, 4, 4, 4, 8, -1.0, 1, None, 0, None) == sp.SP_ERR_UNSUPPORTED
+    # workspace too small / missing
+    assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 4, 64, 1000, 8, 0.1, one, 16, None) == sp.SP_ERR_WORKSPACE
+    assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 4, 64, 1000, 8, 0.1, None, 0, None) == sp.SP_ERR_WORKSPACE
+    assert b"workspace" in L.sp_last_error()
+    # empty batches are legal no-ops
+    assert L.sp_attn_prefill(ctypes.byref(d), one, one, one, one, one, 0, 1, 0, 0, 0, 8, 0.1, 1, None, 0, None) == sp.SP_OK
+    assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 0, 1, 0, 8, 0.1, None, 0, None) == sp.SP_OK

@@ -1,0 +1,223 @@
+"""GPU parity: the HIP library (through the C ABI) against the fp64 oracle on the same seeded
+bits.  Floating point: max abs error <= 1e-2 (bf16 in, fp32 accumulate, bf16 out).  Cache
+images after sp_kv_append: bit-exact, canaries included."""
+import hashlib
+
+import numpy as np
+import pytest
+
+import workloads as W
+from harness import TOL, GpuRunner, OracleRunner, bits_of, dev_i32, gather_rows, report_err, sample_rows, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def custom_workload(name, lens_total, ctx, Hq, Hkv, d, kind, seed):
+    """Sequences with `ctx` tokens cached (a 'fill' step) followed by one `kind` step over the rest."""
+    lens_total, ctx = np.asarray(lens_total, np.int32), np.asarray(ctx, np.int32)
+    rng = np.random.default_rng(seed)
+    bt, pool = W.make_block_table(rng, lens_total)
+
+    def gen():
+        r = np.random.default_rng(seed + 1)
+        if ctx.sum() > 0:
+            yield W._chunk_step(r, "fill", ctx, np.zeros_like(ctx), Hq, Hkv, d)
+        yield W._chunk_step(r, kind, lens_total - ctx, ctx, Hq, Hkv, d)
+
+    return W.Workload(name, Hq, Hkv, d, pool, bt, lens_total, gen)
+
+
+def run_full_compare(w, check_cache=True):
+    """Every step on both sides, every attention output compared element by element."""
+    g, o = GpuRunner(w), OracleRunner(w)
+    worst = 0.0
+    for i, st in enumerate(w.steps()):
+        g.append(st)
+        o.append(st)
+        if st.kind != "fill":
+            worst = max(worst, report_err(f"{w.name} step {i} {st.kind}", g.attend(st), o.attend(st)))
+    if check_cache:
+        gk, gv = g.cache_bits()
+        assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp), "cache image differs from the oracle's"
+    assert worst <= TOL
+    return worst
+
+
+# ------------------------------------------------------------------ sp_kv_append
+def test_append_bit_exact_ragged_with_prefix():
+    lens = [45, 16, 0, 3, 300, 1]
+    ctx = [13, 0, 0, 2, 17, 0]
+    for Hkv, d in ((1, 128), (8, 128), (2, 64)):
+        w = custom_workload(f"append-{Hkv}-{d}", lens, ctx, 2 * Hkv, Hkv, d, "prefill", seed=11)
+        g, o = GpuRunner(w), OracleRunner(w)
+        for st in w.steps():
+            g.append(st)
+            o.append(st)
+        gk, gv = g.cache_bits()
+        assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp)
+        assert (o.kp == W.CANARY).any()            # holes exist and were compared too
+
+
+def test_append_ignores_out_of_range_pages():
+    """A block-table entry outside the pool must not become a wild store."""
+    import paper_2507_11830_amd as sp
+
+    w = custom_workload("append-bad", [40], [0], 2, 1, 64, "prefill", seed=12)
+    g = GpuRunner(w)
+    st = next(w.steps())
+    bad = w.block_table.copy()
+    bad[0, 1] = w.num_pages + 1000
+    g.bt = dev_i32(bad)
+    with pytest.raises(sp.SpError):
+        sp.sp_debug_validate_metadata(g.cache, dev_i32(st.seq_lens), g.bt)
+    g.append(st)
+    gk, _ = g.cache_bits()
+    good_page = w.block_table[0, 0]
+    assert np.array_equal(gk[good_page, 0], st.k_new[:16, 0])
+    untouched = np.ones(w.num_pages, bool)
+    untouched[[w.block_table[0, 0], w.block_table[0, 2]]] = False
+    assert (gk[untouched] == W.CANARY).all()
+
+
+# ------------------------------------------------------------------ small shapes, every element
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 1, 128), (2, 1, 64), (32, 8, 128), (4, 4, 64), (6, 2, 128), (1, 1, 128)])
+def test_prefill_small_ragged(Hq, Hkv, d):
+    lens = [1, 17, 63, 64, 65, 300, 0, 130]
+    ctx = [0, 5, 0, 31, 64, 111, 0, 129]
+    run_full_compare(custom_workload(f"prefill-{Hq}-{Hkv}-{d}", lens, ctx, Hq, Hkv, d, "prefill", seed=21))
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 1, 128), (2, 1, 64), (32, 8, 128), (6, 2, 128), (40, 1, 64)])
+def test_decode_small_ragged(Hq, Hkv, d):
+    lens = np.array([1, 15, 16, 17, 127, 128, 129, 255, 256, 257, 1000, 2049])
+    run_full_compare(custom_workload(f"decode-{Hq}-{Hkv}-{d}", lens, lens - 1, Hq, Hkv, d, "decode", seed=31))
+
+
+def test_decode_with_empty_sequences():
+    import torch
+    import paper_2507_11830_amd as sp
+
+    w = custom_workload("decode-empty", [40, 7], [39, 6], 8, 1, 128, "decode", seed=32)
+    g, o = GpuRunner(w), OracleRunner(w)
+    for st in w.steps():
+        g.append(st)
+        o.append(st)
+    seq_lens = np.array([40, 0], np.int32)
+    q = to_dev(st.q)
+    out = torch.full_like(q, 7.0)
+    ws = torch.empty(sp.sp_attn_decode_workspace_size(2, 40, 8, 128), dtype=torch.uint8, device="cuda")
+    sp.sp_attn_decode(g.cache, q, out, dev_i32(seq_lens), g.bt, 40, float(w.scale), ws)
+    got = bits_of(out)
+    want = o.o.attn_decode(o.kp, o.vp, st.q, seq_lens, w.block_table, w.scale)
+    assert (got[1] == 0).all()
+    assert report_err("decode-empty", got, want) <= TOL
+    # all sequences empty: max_seq_len = 0, no workspace needed
+    out2 = torch.full_like(q, 7.0)
+    sp.sp_attn_decode(g.cache, q, out2, dev_i32([0, 0]), g.bt, 0, float(w.scale), None)
+    assert (bits_of(out2) == 0).all()
+
+
+def test_decode_equals_prefill_row_on_gpu():
+    """The two modes read the same cache and agree: decode at length t vs prefill row t-1."""
+    import torch
+    import paper_2507_11830_amd as sp
+
+    w = W.c2_prefill(batch=2, seqlen=700)
+    g = GpuRunner(w)
+    st = next(w.steps())
+    g.append(st)
+    full = W.bf16_bits_to_f64(g.attend(st))
+    ws = torch.empty(sp.sp_attn_decode_workspace_size(2, 700, w.Hq, w.d), dtype=torch.uint8, device="cuda")
+    for t in (1, 16, 333, 700):
+        qd = np.stack([st.q[st.cu_new[s] + t - 1] for s in range(2)])
+        out = torch.empty((2, w.Hq, w.d), dtype=torch.bfloat16, device="cuda")
+        sp.sp_attn_decode(g.cache, to_dev(qd), out, dev_i32([t, t]), g.bt, t, float(w.scale), ws)
+        dec = W.bf16_bits_to_f64(bits_of(out))
+        ref = np.stack([full[st.cu_new[s] + t - 1] for s in range(2)])
+        assert np.abs(dec - ref).max() <= TOL
+
+
+def test_results_are_bitwise_reproducible():
+    w = custom_workload("repro", [777, 300], [100, 0], 8, 1, 128, "prefill", seed=41)
+    g = GpuRunner(w)
+    last = None
+    for st in w.steps():
+        g.append(st)
+        last = st
+    a, b = g.attend(last), g.attend(last)
+    assert np.array_equal(a, b)
+    w2 = custom_workload("repro-d", [3000, 900], [2999, 899], 8, 1, 128, "decode", seed=42)
+    g2 = GpuRunner(w2)
+    for st in w2.steps():
+        g2.append(st)
+        last = st
+    assert np.array_equal(g2.attend(last), g2.attend(last))
+
+
+# ------------------------------------------------------------------ the five configurations
+def test_c1_tiny_gqa_every_step():
+    run_full_compare(W.c1_tiny())
+
+
+def test_c2_70b_prefill_full():
+    run_full_compare(W.c2_prefill())
+
+
+def test_c3_70b_decode_full():
+    run_full_compare(W.c3_decode())
+
+
+def test_c4_mixed_chunked_scaled_full():
+    """Same recipe at 1/4 of the lengths: every element of every chunk step compared."""
+    run_full_compare(W.c4_chunked(batch=12, median=375.0, lo=16, hi=2048, chunk=128))
+
+
+def test_c4_mixed_chunked_full_size_sampled():
+    w = W.c4_chunked()
+    g, o = GpuRunner(w), OracleRunner(w)
+    rng = np.random.default_rng(4)
+    worst = 0.0
+    for i, st in enumerate(w.steps()):
+        g.append(st)
+        o.append(st)
+        if st.kind == "fill":
+            continue
+        out = g.attend(st)
+        rs, rt, rh = sample_rows(rng, st, w.Hq, 256)
+        worst = max(worst, report_err(f"C4 step {i} sampled", gather_rows(out, st, rs, rt, rh), o.attend_rows(st, rs, rt, rh)))
+        assert np.isfinite(W.bf16_bits_to_f32(out)).all()
+    gk, gv = g.cache_bits()
+    assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp)
+    assert worst <= TOL
+
+
+def test_c5_long_context_shift_same_cache():
+    """32768-token prefill (sampled rows), then decode steps on the SAME cache and block table:
+    the pages written by the prefill step are byte-identical before and after the decode phase."""
+    w = W.c5_long(decode_steps=32)
+    g, o = GpuRunner(w), OracleRunner(w)
+    rng = np.random.default_rng(5)
+    steps = w.steps()
+    st = next(steps)
+    g.append(st)
+    o.append(st)
+    out = g.attend(st)
+    rs, rt, rh = sample_rows(rng, st, w.Hq, 768)
+    assert report_err("C5a sampled", gather_rows(out, st, rs, rt, rh), o.attend_rows(st, rs, rt, rh)) <= TOL
+    assert np.isfinite(W.bf16_bits_to_f32(out)).all()
+    full_pages = w.block_table[0, : 32768 // 16]
+    gk, gv = g.cache_bits()
+    h0 = hashlib.sha256(gk[full_pages].tobytes() + gv[full_pages].tobytes()).hexdigest()
+    worst = 0.0
+    for i, st in enumerate(steps):
+        g.append(st)
+        o.append(st)
+        worst = max(worst, report_err(f"C5b decode step {i}", g.attend(st), o.attend(st)))
+    gk, gv = g.cache_bits()
+    assert hashlib.sha256(gk[full_pages].tobytes() + gv[full_pages].tobytes()).hexdigest() == h0
+    assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp)
+    assert worst <= TOL
+
+
+def test_c5c_8b_shape_decode_batch():
+    run_full_compare(W.c5c_decode_8b(batch=32), check_cache=False)
