@@ -1,0 +1,296 @@
+#!/usr/bin/env python3
+"""Benchmark of the Shift Parallelism attention hot path on one MI355X.
+
+A "step" is one pass of the whole hot path at the Llama-3.3-70B head-shard shape (8 query
+heads / 1 KV head, head_dim 128), inputs resident in HBM:
+
+    sp_kv_append (8192 tokens)  ->  sp_attn_prefill   [SP-mode prefill, 4 x 2048 tokens, causal]
+    sp_kv_append (64 tokens)    ->  sp_attn_decode    [TP-mode decode, 64 sequences with
+                                                       contexts U{512..8192}; split + combine]
+
+Every phase is bracketed by HIP events on the launch stream inside the timed region, so the
+prefill TFLOP/s and the decode GB/s are per-phase figures; ``ms_per_step`` is the wall time
+of the whole step.  The decode phase rotates over several copies of its KV pool so that its
+working set (about 140 MB, smaller than the 256 MB last-level cache) is read cold from HBM.
+
+Prints ONE JSON line.  ``value`` is the prefill attention TFLOP/s (algorithmic flops of the
+step's prefill / mean prefill-phase duration); the decode GB/s rides along in ``decode``.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
+
+
+def _dev_bf16(u16):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def _dev_i32(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+class PrefillJob:
+    """SP-mode prefill workload resident on the device."""
+
+    def __init__(self, sp, w):
+        import torch
+
+        self.sp, self.w = sp, w
+        st = next(w.steps())
+        self.st = st
+        self.cache = sp.KVCache.empty(w.num_pages, w.Hkv, w.d)
+        self.bt = _dev_i32(w.block_table)
+        self.k, self.v, self.q = _dev_bf16(st.k_new), _dev_bf16(st.v_new), _dev_bf16(st.q)
+        self.out = torch.empty_like(self.q)
+        self.cu, self.ctx = _dev_i32(st.cu_new), _dev_i32(st.ctx_lens)
+        self.max_q, self.max_kv = int(st.new_lens.max()), int(st.seq_lens.max())
+        import workloads as W
+
+        self.flops = W.prefill_flops(st, w.Hq, w.d)
+        self.append_bytes = W.append_bytes(int(st.new_lens.sum()), w.Hkv, w.d)
+
+    def append(self):
+        self.sp.sp_kv_append(self.cache, self.k, self.v, self.cu, self.ctx, self.bt)
+
+    def attend(self):
+        self.sp.sp_attn_prefill(self.cache, self.q, self.out, self.cu, self.ctx, self.bt, self.max_q,
+                                self.max_kv, float(self.w.scale))
+
+
+class DecodeJob:
+    """TP-mode decode workload: `copies` independent KV pools, rotated so reads come from HBM."""
+
+    def __init__(self, sp, w, copies):
+        import torch
+        import workloads as W
+
+        self.sp, self.w = sp, w
+        steps = list(w.steps())
+        fill, dec = steps[0], steps[1]
+        self.dec = dec
+        self.bt = _dev_i32(w.block_table)
+        self.caches = []
+        k_fill, v_fill = _dev_bf16(fill.k_new), _dev_bf16(fill.v_new)
+        cu_f, ctx_f = _dev_i32(fill.cu_new), _dev_i32(fill.ctx_lens)
+        for _ in range(copies):
+            c = sp.KVCache.empty(w.num_pages, w.Hkv, w.d)
+            sp.sp_kv_append(c, k_fill, v_fill, cu_f, ctx_f, self.bt)
+            self.caches.append(c)
+        del k_fill, v_fill
+        self.k, self.v, self.q = _dev_bf16(dec.k_new), _dev_bf16(dec.v_new), _dev_bf16(dec.q)
+        self.out = torch.empty_like(self.q)
+        self.cu, self.ctx = _dev_i32(dec.cu_new), _dev_i32(dec.ctx_lens)
+        self.seq_lens = _dev_i32(dec.seq_lens)
+        self.max_len = int(dec.seq_lens.max())
+        need = sp.sp_attn_decode_workspace_size(w.batch, self.max_len, w.Hq, w.d)
+        self.ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+        self.bytes = W.decode_bytes(dec.seq_lens, w.Hq, w.Hkv, w.d)
+        self.i = 0
+
+    def next_cache(self):
+        self.i = (self.i + 1) % len(self.caches)
+        return self.caches[self.i]
+
+    def append(self, cache):
+        self.sp.sp_kv_append(cache, self.k, self.v, self.cu, self.ctx, self.bt)
+
+    def attend(self, cache):
+        self.sp.sp_attn_decode(cache, self.q, self.out, self.seq_lens, self.bt, self.max_len,
+                               float(self.w.scale), self.ws)
+
+
+def time_phases(fns, steps, warmup):
+    """Runs the phase functions in order `steps` times; returns (wall ms/step, [mean ms per phase])."""
+    import torch
+
+    for _ in range(warmup):
+        for f in fns:
+            f()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        ev[s][0].record()
+        for i, f in enumerate(fns):
+            f()
+            ev[s][i + 1].record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    per = [float(np.mean([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(steps)])) for i in range(len(fns))]
+    return wall, per
+
+
+def cpu_baseline(w, st, budget_s=12.0):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample of the
+    prefill rows (rows drawn uniformly; work = 4*d flops per visible (query, key) pair)."""
+    import oracle
+    import workloads as W
+
+    kp, vp = w.empty_cache()
+    oracle.kv_append(kp, vp, st.k_new, st.v_new, st.cu_new, st.ctx_lens, w.block_table)
+    rng = np.random.default_rng(0)
+    lens = st.new_lens
+
+    def draw(n):
+        rs = rng.integers(0, len(lens), size=n).astype(np.int32)
+        rt = np.array([rng.integers(0, lens[s]) for s in rs], dtype=np.int32)
+        rh = rng.integers(0, w.Hq, size=n).astype(np.int32)
+        flops = int(sum(4 * w.d * (int(st.ctx_lens[s]) + int(t) + 1) for s, t in zip(rs, rt)))
+        return rs, rt, rh, flops
+
+    def run(n):
+        rs, rt, rh, flops = draw(n)
+        t0 = time.perf_counter()
+        oracle.attn_prefill_rows(kp, vp, st.q, st.cu_new, st.ctx_lens, w.block_table, w.scale, rs, rt, rh)
+        return flops, time.perf_counter() - t0
+
+    f, t = run(2048)                       # pilot
+    n = int(min(len(lens) * int(lens.max()) * w.Hq, max(2048, 2048 * budget_s / max(t, 1e-3))))
+    f, t = run(n)
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": f / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n} uniformly drawn (sequence, token, head) rows of the same 4x2048 prefill, fp64, {t:.1f} s"}
+
+
+def extra_long_prefill(sp, iters=5):
+    """32768-token single-sequence prefill (values from torch's seeded GPU generator)."""
+    import torch
+    import workloads as W
+
+    w = W.c5_long(decode_steps=0)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    T = 32768
+    k = torch.randn((T, 1, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((T, 1, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((T, 8, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    cache = sp.KVCache.empty(w.num_pages, 1, 128)
+    bt, cu, ctx = _dev_i32(w.block_table), _dev_i32([0, T]), _dev_i32([0])
+    sp.sp_kv_append(cache, k, v, cu, ctx, bt)
+    fn = lambda: sp.sp_attn_prefill(cache, q, out, cu, ctx, bt, T, T, float(w.scale))
+    _, per = time_phases([fn], iters, 1)
+    flops = 4 * 128 * 8 * T * (T + 1) // 2
+    return {"workload": "C5a 1x32768-token causal prefill, 8q/1kv, d=128", "ms": per[0],
+            "TFLOPs": flops / per[0] / 1e9, "frac_of_bf16_peak": flops / per[0] / 1e9 / PEAK_BF16_TFLOPS}
+
+
+def extra_big_decode(sp, iters=10):
+    """Llama-3.1-8B shape decode batch: 128 sequences, 32q/8kv, contexts U{1024..16384} (~4.7 GB of
+    KV, far beyond the last-level cache).  Values from torch's seeded GPU generator."""
+    import torch
+    import workloads as W
+
+    w = W.c5c_decode_8b()
+    lens = w.total_lens
+    cache = sp.KVCache.empty(w.num_pages, 8, 128)
+    g = torch.Generator(device="cuda").manual_seed(6)
+    for pool in (cache.k_pages, cache.v_pages):       # fill in slabs to bound temporary memory
+        flat = pool.view(-1)
+        slab = 1 << 28
+        for a in range(0, flat.numel(), slab):
+            n = min(slab, flat.numel() - a)
+            flat[a:a + n] = torch.randn(n, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((w.batch, 32, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    bt, sl = _dev_i32(w.block_table), _dev_i32(lens)
+    mx = int(lens.max())
+    ws = torch.empty(sp.sp_attn_decode_workspace_size(w.batch, mx, 32, 128), dtype=torch.uint8, device="cuda")
+    fn = lambda: sp.sp_attn_decode(cache, q, out, sl, bt, mx, float(w.scale), ws)
+    _, per = time_phases([fn], iters, 2)
+    nbytes = W.decode_bytes(lens, 32, 8, 128)
+    return {"workload": "C5c 128-sequence decode, 32q/8kv, d=128, contexts U{1024..16384}", "ms": per[0],
+            "GBps": nbytes / per[0] / 1e6, "frac_of_hbm_peak": nbytes / per[0] / 1e6 / PEAK_HBM_GBPS,
+            "kv_bytes": nbytes}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-extras", action="store_true", help="skip the C5a / C5c side measurements")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs one GPU's head shard only (no collectives, no sharding); "
+                 "use --gpus 1")
+
+    import torch
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    import paper_2507_11830_amd as sp
+    import workloads as W
+
+    sp.lib()   # fail loudly if the HIP library is missing
+    wp, wd = W.c2_prefill(), W.c3_decode()
+    pre = PrefillJob(sp, wp)
+    copies = 8
+    dec = DecodeJob(sp, wd, copies)
+    state = {}
+
+    def ph_append_p():
+        pre.append()
+
+    def ph_prefill():
+        pre.attend()
+
+    def ph_append_d():
+        state["c"] = dec.next_cache()
+        dec.append(state["c"])
+
+    def ph_decode():
+        dec.attend(state["c"])
+
+    wall, per = time_phases([ph_append_p, ph_prefill, ph_append_d, ph_decode], args.steps, args.warmup)
+    t_app_p, t_pre, t_app_d, t_dec = per
+    tflops = pre.flops / t_pre / 1e9
+    gbps = dec.bytes / t_dec / 1e6
+    res = {
+        "metric": "prefill attn TFLOP/s (value) + decode KV GB/s (decode.value) at 70B head shard",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C2 (4x2048-token causal prefill) + C3 (64-sequence decode, contexts U{512..8192}, "
+                               "cold KV) at 8 q heads / 1 kv head, head_dim 128, 16-token pages",
+                   "prefill_tokens": int(pre.st.new_lens.sum()), "decode_batch": wd.batch,
+                   "decode_kv_tokens": int(dec.dec.seq_lens.sum()), "decode_pool_copies": copies},
+        "phases_ms": {"kv_append_prefill": t_app_p, "attn_prefill": t_pre, "kv_append_decode": t_app_d,
+                      "attn_decode_split_plus_combine": t_dec},
+        "decode": {"value": gbps, "unit": "GB/s", "frac_of_hbm_peak": gbps / PEAK_HBM_GBPS,
+                   "algorithmic_bytes": dec.bytes},
+        "kv_append_GBps": pre.append_bytes / t_app_p / 1e6,
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None, "kernel": "prefill_kernel",
+                     "algorithmic_flops": pre.flops},
+        "roofline_decode": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                            "frac": gbps / PEAK_HBM_GBPS, "traffic": None,
+                            "kernel": "decode_split_kernel + decode_combine_kernel"},
+    }
+    if not args.no_extras:
+        res["other_workloads"] = [extra_long_prefill(sp), extra_big_decode(sp)]
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wp, pre.st)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -128,6 +128,15 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
                                const int32_t *block_table, int32_t batch,
                                int32_t max_pages_per_seq);
 
+/*
+ * sp_debug_set_tuning — process-wide override of an internal launch parameter, for tuning
+ * sweeps and tests.  Not thread-safe against concurrent attention calls.  Keys:
+ *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a power of two in
+ *                   [128, 1024].  Changes what sp_attn_decode_workspace_size returns.
+ * Returns SP_OK, SP_ERR_NULL or SP_ERR_UNSUPPORTED (unknown key / value out of range).
+ */
+int sp_debug_set_tuning(const char *key, int32_t value);
+
 const char *sp_status_string(int status); /* static string                              */
 const char *sp_last_error(void);          /* thread-local detail of the last failure    */
 int sp_version(void);

@@ -24,7 +24,8 @@ SP_ERR_HIP = -5
 
 EXPORTS = (
     "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_attn_prefill_workspace_size",
-    "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_status_string",
+    "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_set_tuning",
+    "sp_status_string",
     "sp_last_error", "sp_version",
 )
 
@@ -69,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.sp_attn_decode_workspace_size.restype = sz
         L.sp_debug_validate_metadata.argtypes = [cd, vp, vp, i32, i32]
         L.sp_debug_validate_metadata.restype = ctypes.c_int
+        L.sp_debug_set_tuning.argtypes = [ctypes.c_char_p, i32]
+        L.sp_debug_set_tuning.restype = ctypes.c_int
         L.sp_status_string.argtypes = [ctypes.c_int]
         L.sp_status_string.restype = ctypes.c_char_p
         L.sp_last_error.restype = ctypes.c_char_p
@@ -178,3 +181,7 @@ def sp_debug_validate_metadata(cache: KVCache, seq_lens, block_table) -> None:
     batch, max_pages = block_table.shape
     _check(lib().sp_debug_validate_metadata(ctypes.byref(cache.desc), _ptr(seq_lens), _ptr(block_table),
                                             batch, max_pages))
+
+
+def sp_debug_set_tuning(key: str, value: int) -> None:
+    _check(lib().sp_debug_set_tuning(key.encode(), int(value)))

@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
 #include <vector>
 
 #include "sp_common.h"
@@ -143,6 +144,17 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
     }
   }
   return SP_OK;
+}
+
+int sp_debug_set_tuning(const char *key, int32_t value) {
+  if (!key) return fail(SP_ERR_NULL, "tuning key is NULL");
+  if (!strcmp(key, "decode_chunk")) {
+    if (value != 0 && (value < 128 || value > 1024 || (value & (value - 1))))
+      return fail(SP_ERR_UNSUPPORTED, "decode_chunk=%d (0, or a power of two in [128, 1024])", value);
+    set_decode_chunk(value);
+    return SP_OK;
+  }
+  return fail(SP_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
 }
 
 const char *sp_status_string(int status) {

@@ -34,6 +34,9 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
                    int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
                    hipStream_t stream);
 
+// Tuning hooks behind sp_debug_set_tuning (0 restores the built-in heuristic).
+void set_decode_chunk(int chunk);
+
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);
 int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
                   const int32_t *block_table, int batch, int max_pages, int max_seq_len,
