@@ -226,6 +226,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true", help="skip the C5a / C5c side measurements")
+    ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5c"],
+                    help="main = the step described above; c5a / c5c = only that side workload "
+                         "(used for per-kernel profiles)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -241,6 +244,10 @@ def main():
     import workloads as W
 
     sp.lib()   # fail loudly if the HIP library is missing
+    if args.workload != "main":
+        fn = extra_long_prefill if args.workload == "c5a" else extra_big_decode
+        print(json.dumps(fn(sp, iters=args.steps)))
+        return
     wp, wd = W.c2_prefill(), W.c3_decode()
     pre = PrefillJob(sp, wp)
     copies = 8

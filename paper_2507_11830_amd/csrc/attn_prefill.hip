@@ -14,9 +14,67 @@
 //
 // Bound: bf16 MFMA (4 * head_dim flops per visible (query, key) pair per head).  K/V HBM
 // traffic is ~1/(8*columns) of that in bytes and is served mostly from L2.
+#include <type_traits>
+
 #include "attn_tile.h"
 
+// Compile-time switches for timing experiments (results become wrong when non-zero):
+// 1 no exp, 2 no PV MFMAs, 4 no QK MFMAs, 8 no tile staging, 16 no softmax.
+#ifndef SP_ABLATE
+#define SP_ABLATE 0
+#endif
+#ifndef SP_TRACE
+#define SP_TRACE 0
+#endif
+#ifndef SP_STAGE_SGB
+#define SP_STAGE_SGB 1
+#endif
+#ifndef SP_PRIO
+#define SP_PRIO 3
+#endif
+#if SP_TRACE
+#define SP_STAMP(slot)                                                                       \
+  do {                                                                                       \
+    if (a.trace && blockIdx.x == 8 && blockIdx.y == 0 && lane == 0 && h < 128)              \
+      a.trace[(w * 128 + h) * 4 + (slot)] = __builtin_readcyclecounter();                    \
+  } while (0)
+#else
+#define SP_STAMP(slot) do { } while (0)
+#endif
+
 namespace sp {
+
+// Scheduling pattern of a software-pipelined MFMA sequence of N operands starting at fused
+// index I0 (indices below NPV are V^T operands = 2 LDS reads, the rest K operands = 1 read):
+// PFD operand reads up front, then "read operand i+PFD, MFMA i".  The group sizes must be
+// compile-time constants, hence the recursion.
+template <int I, int N, int I0, int NPV, int PFD>
+__device__ __forceinline__ void sgb_prologue() {
+  if constexpr (I < PFD && I < N) {
+    if constexpr (I0 + I < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    sgb_prologue<I + 1, N, I0, NPV, PFD>();
+  }
+}
+// With STAGE, the tile-staging instructions that share the region are dealt out between the
+// MFMAs: a few VALU (address arithmetic) after every MFMA, one vector-memory load after every
+// second one, one LDS write after every fourth, so they issue in the shadow of the matrix pipe.
+template <int I, int N, int I0, int NPV, int PFD, bool STAGE>
+__device__ __forceinline__ void sgb_steady() {
+  if constexpr (I < N) {
+    if constexpr (I + PFD < N) {
+      if constexpr (I0 + I + PFD < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (STAGE) {
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+      if constexpr (I % 4 == 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+      if constexpr (I % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    sgb_steady<I + 1, N, I0, NPV, PFD, STAGE>();
+  }
+}
 
 struct PrefillArgs {
   const char *k_pages, *v_pages, *q;
@@ -24,6 +82,10 @@ struct PrefillArgs {
   const int32_t *cu_q, *ctx_lens, *block_table;
   int max_pages, num_pages, Hq, Hkv, gshift, n_hgroups, ntiles_x;
   float sl2e;  // scale * log2(e)
+  float tau;   // lazy-rescale threshold in raw score units (8 / sl2e)
+  int pp_interleave;  // ping-pong groups: 0 = waves {0-3},{4-7}; 1 = even/odd waves
+  int ablate;         // unused
+  long long *trace;   // SP_TRACE builds only: per-wave timestamps of one workgroup
 };
 
 template <int D, int NW, int QB, int KVT>
@@ -39,7 +101,8 @@ __global__ __launch_bounds__(NW * 64) void prefill_kernel(PrefillArgs a) {
   extern __shared__ __align__(16) char smem_raw[];
   lds_char *smem = (lds_char *)smem_raw;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches on it scalar
   const int col = lane & 31, half = lane >> 5;
   const int seq = blockIdx.y / a.n_hgroups, hg = blockIdx.y - seq * a.n_hgroups;
   const int tile = a.ntiles_x - 1 - (int)blockIdx.x;  // longest key ranges are dispatched first
@@ -242,29 +305,362 @@ __global__ __launch_bounds__(NW * 64) void prefill_kernel(PrefillArgs a) {
   }
 }
 
-template <int D, int NW, int QB, int KVT>
-static int launch_cfg(const PrefillArgs &a0, int batch, int max_q_len, hipStream_t stream) {
+// Ping-pong variant (NW = 8 waves, 32 columns per wave).  The waves form two groups of four,
+// one wave of each group per SIMD.  Time is cut into half-steps separated by workgroup
+// barriers; in every half-step one group runs its MFMA phase (PV of the previous tile, then
+// QK^T of the current one) while the other runs its softmax phase on the VALU, and they swap
+// in the next half-step.  The matrix pipe of a SIMD therefore always has a wave feeding it
+// while the other wave's exponentials run beside it — barrier-synchronised waves that all
+// do the same phase at the same time leave the MFMA pipe idle during every softmax.
+//
+// LDS: K[2] and V[2] tile buffers.  Tile staging (global -> registers -> LDS one round later)
+// rides in the MFMA phases; page ids are fetched one further round ahead so no load waits on
+// a block-table lookup.
+//
+// The running max is only moved when some column's tile max exceeds it by more than 2^8 in
+// the exponent (kTau); otherwise weights are taken against the stale max (bounded by 2^8,
+// harmless in fp32/bf16) and the O accumulators need no rescale.
+template <int D, int KVT, int PFD>
+__global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
   using G = TileGeom<D>;
+  constexpr int NT = 512, COLS = 256, KB = KVT / 32;
+  constexpr int KBYTES = KVT * G::kKStride, VBYTES = KVT * G::kVStride;
+  constexpr int CPR = G::kChunksPerRow;
+  constexpr int NCH = KVT * CPR / NT;
+  static_assert(KVT * CPR % NT == 0 && NCH >= 1, "tile does not divide over the workgroup");
+  extern __shared__ __align__(16) char smem_raw[];
+  lds_char *smem = (lds_char *)smem_raw;
+  auto kbuf = [&](int t) { return smem + (t & 1) * KBYTES; };
+  auto vbuf = [&](int t) { return smem + 2 * KBYTES + (t & 1) * VBYTES; };
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches on it scalar
+  const int col = lane & 31, half = lane >> 5;
+  const int grp = w >> 2;  // wave-uniform; waves w and w+4 share a SIMD: one wave of each group per SIMD
+  const int seq = blockIdx.y / a.n_hgroups, hg = blockIdx.y - seq * a.n_hgroups;
+  const int tile = a.ntiles_x - 1 - (int)blockIdx.x;  // longest key ranges are dispatched first
+  const int tpt = COLS >> a.gshift;
+  const int q0 = a.cu_q[seq];
+  const int q_len = a.cu_q[seq + 1] - q0;
+  const int tok0 = tile * tpt;
+  if (tok0 >= q_len) return;
+  const int ctx = a.ctx_lens[seq];
+  const int kv_end = ctx + min(q_len, tok0 + tpt);
+  const int kvh = (hg << a.gshift) / (a.Hq / a.Hkv);
+  const int32_t *bt_row = a.block_table + (long)seq * a.max_pages;
+  const int gmask = (1 << a.gshift) - 1;
+
+  // ---- this lane's column and the resident Q^T operands
+  bf16x8 qreg[G::kDSteps];
+  const int C = w * 32 + col;
+  const int token = tok0 + (C >> a.gshift);
+  const int head = (hg << a.gshift) | (C & gmask);
+  const bool valid = token < q_len;
+  const int lim = valid ? ctx + token + 1 : 1;
+  const long out_off = ((long)(q0 + token) * a.Hq + head) * (D * 2);
+#pragma unroll
+  for (int s = 0; s < G::kDSteps; ++s) {
+    if (valid) {
+      qreg[s] = *reinterpret_cast<const bf16x8 *>(a.q + out_off + 32 * s + 16 * half);
+    } else {
+      u32x4 z = {0, 0, 0, 0};
+      qreg[s] = *reinterpret_cast<bf16x8 *>(&z);
+    }
+  }
+  const int wtok_first = tok0 + ((w * 32) >> a.gshift);
+  const int wtok_last = tok0 + (((w + 1) * 32 - 1) >> a.gshift);
+  const int wlim_max = wtok_first < q_len ? ctx + min(wtok_last, q_len - 1) + 1 : 0;
+  const int wlim_min = wtok_last < q_len ? ctx + wtok_first + 1 : 1;
+
+  f32x16 o[G::kDBlocks];
+#pragma unroll
+  for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_used = -INFINITY, l = 0.f;
+  f32x16 sacc[KB];
+  bf16x8 pop[KB][2];
+
+  const int T = (kv_end + KVT - 1) / KVT;  // key tiles this workgroup walks
+  const int sd = 1 - grp;  // tile offset of a group's staging: K one tile ahead, V for the current tile
+
+  // ---- staging, split by group: the first group moves the K tiles, the second the V tiles,
+  // each during its own MFMA phase, where the wave mostly waits on the matrix pipe and has issue
+  // slots to spare (the softmax phase has none).  Each thread handles NCH2 16-byte chunks.
+  // Staging is branch-free: a conditional load leaves the waitcnt pass no choice but a full
+  // vmcnt(0) at the join.  Rows past the end of the sequence are redirected to its last valid
+  // row (finite data; their weights are masked to zero), tiles past the last one to the last.
+  // With 256 threads per group, chunk i of a thread always lies in page i of the tile, in the
+  // same row-of-page and column for every i: the page ids are wave-uniform (fetched with scalar
+  // loads during the softmax phase, which has no LDS traffic to disturb) and the per-tile
+  // vector arithmetic is three or four ops per chunk.
+  constexpr int NCH2 = KVT * CPR / 256;
+  constexpr int RPC = 256 / CPR;             // tile rows between two chunks of one thread
+  static_assert(64 / CPR <= kPage, "the rows one wave stages must lie in one page");
+  u32x4 sreg[NCH2];
+  int spg[NCH2];                             // page ids of the tile to load next (SGPRs)
+  const int last_kv = kv_end - 1, last_page = last_kv >> 4;
+  const int gt = tid & 255;                  // thread index inside the group (waves 0-3 / 4-7)
+  const int st_row0 = gt / CPR;              // row of chunk 0 inside the tile
+  const int st_wrow0 = __builtin_amdgcn_readfirstlane(st_row0);  // a wave's rows share one page
+  const char *st_col = (grp ? a.v_pages : a.k_pages) + kvh * (kPage * D * 2) + (gt % CPR) * 16;
+  const int sstride = grp ? G::kVStride : G::kKStride;
+  const int st_lds0 = st_row0 * sstride + (gt % CPR) * 16;
+  const unsigned pool_rows_per_page = (unsigned)a.Hkv * kPage;  // rows of all heads in one page
+  // row-of-page of chunk i: constant, except in pages at or past the sequence's last page,
+  // where it is folded back onto a written row (rows past the end only feed masked weights)
+  int st_rop[NCH2], st_rop_last[NCH2];
+#pragma unroll
+  for (int i = 0; i < NCH2; ++i) {
+    st_rop[i] = (st_row0 + i * RPC) & 15;
+    st_rop_last[i] = min(st_rop[i], last_kv & 15);
+  }
+  auto page_ids = [&](int t) {  // scalar loads: t and the indices are wave-uniform
+    const int tt = min(t, T - 1);
+#pragma unroll
+    for (int i = 0; i < NCH2; ++i)
+      spg[i] = bt_row[min((tt * KVT + i * RPC + st_wrow0) >> 4, last_page)];
+  };
+  auto load_tile = [&](int t) {
+    const int tt = min(t, T - 1);
+#pragma unroll
+    for (int i = 0; i < NCH2; ++i) {
+      const bool tail = ((tt * KVT + i * RPC + st_wrow0) >> 4) >= last_page;  // uniform
+      const unsigned page = (unsigned)min(max(spg[i], 0), a.num_pages - 1);  // no wild loads on bad metadata
+      const unsigned rowidx = page * pool_rows_per_page + (unsigned)(tail ? st_rop_last[i] : st_rop[i]);
+      sreg[i] = *reinterpret_cast<const u32x4 *>(st_col + (size_t)rowidx * (D * 2));
+    }
+  };
+  auto write_tile = [&](int t) {
+    lds_char *buf = (grp ? vbuf(t) : kbuf(t)) + st_lds0;
+#pragma unroll
+    for (int i = 0; i < NCH2; ++i) *(lds_u32x4 *)(buf + i * RPC * sstride) = sreg[i];
+  };
+
+  // ---- the phases of a tile, per wave.  The MFMA phases are written as "all operand reads,
+  // then all MFMAs" and pinned to an interleaved issue order with sched_group_barrier, so that
+  // LDS reads run a fixed distance ahead of the MFMAs that consume them (left alone, the
+  // scheduler places each read right before its use and the matrix pipe waits on LDS latency).
+  // PFD: how many MFMAs ahead of their use the operand reads are issued
+  constexpr int NPV = KB * 2 * G::kDBlocks, NQK = KB * G::kDSteps;
+  // Operand i of the fused sequence "PV of tile tv, then QK^T of tile tk": i < NPV is a V^T
+  // operand (two transposing reads), the rest are K operands (one 16-byte read).
+  auto load_op = [&](int i, const lds_char *vb, const lds_char *kb) -> bf16x8 {
+    if (i < NPV) {
+      int db = i % G::kDBlocks, ks = (i / G::kDBlocks) & 1, b = i / (2 * G::kDBlocks);
+      return lds_read_vt_operand(vb, G::kVStride, 32 * b + 16 * ks + 4 * half, 32 * db, lane);
+    }
+    int j = i - NPV;
+    int s = j % G::kDSteps, b = j / G::kDSteps;
+    return lds_read_k_operand(kb, G::kKStride, 32 * b + col, 2 * s + half);
+  };
+  auto do_mfma = [&](int i, bf16x8 op) {
+    if (i < NPV) {
+      int db = i % G::kDBlocks, ks = (i / G::kDBlocks) & 1, b = i / (2 * G::kDBlocks);
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op, pop[b][ks], o[db], 0, 0, 0);
+    } else {
+      int j = i - NPV;
+      int s = j % G::kDSteps, b = j / G::kDSteps;
+      if (s == 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+      }
+      sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op, qreg[s], sacc[b], 0, 0, 0);
+    }
+  };
+  // Runs operands [I0, I1) software-pipelined: the source order already interleaves "read
+  // operand i+PFD, MFMA i", and sched_group_barrier pins that order through scheduling (left
+  // alone, the scheduler sinks each read to just before its use and the matrix pipe then
+  // waits a full LDS latency per MFMA pair).
+  auto mfma_seq = [&](auto I0c, auto I1c, auto stagec, int t, const lds_char *vb, const lds_char *kb) {
+    constexpr int I0 = decltype(I0c)::value, I1 = decltype(I1c)::value, N = I1 - I0;
+    constexpr bool STAGE = decltype(stagec)::value;
+    if constexpr (STAGE && !(SP_ABLATE & 8)) {  // same scheduling region as the MFMAs: issued in their shadow
+      write_tile(t + sd);    // loaded one round ago
+      load_tile(t + sd + 1);  // its page ids were fetched in the preceding softmax phase
+    }
+    bf16x8 ops[N];
+    if constexpr (SP_ABLATE & 32) {  // timing experiment: MFMAs without their LDS operand traffic
+#pragma unroll
+      for (int i = 0; i < N; ++i) do_mfma(I0 + i, qreg[i % G::kDSteps]);
+      return;
+    }
+    if constexpr (SP_ABLATE & 6) {   // timing experiment: LDS operand traffic without MFMAs
+      u32x4 sink = {0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        bf16x8 v = load_op(I0 + i, vb, kb);
+        sink ^= *reinterpret_cast<u32x4 *>(&v);
+      }
+      if (sink[0] == 0x12345u) o[0][0] += 1.f;
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < PFD && i < N; ++i) ops[i] = load_op(I0 + i, vb, kb);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      if (i + PFD < N) ops[i + PFD] = load_op(I0 + i + PFD, vb, kb);
+      do_mfma(I0 + i, ops[i]);
+    }
+    sgb_prologue<0, N, I0, NPV, PFD>();
+    sgb_steady<0, N, I0, NPV, PFD, STAGE && (SP_STAGE_SGB != 0)>();
+  };
+  using std::integral_constant;
+  using std::true_type;
+  using std::false_type;
+  auto qk = [&](int t) {
+    mfma_seq(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, true_type{}, t, kbuf(t), kbuf(t));
+  };
+  auto pv = [&](int t) {
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV>{}, false_type{}, t, vbuf(t), vbuf(t));
+  };
+  auto pv_qk = [&](int t) {
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, true_type{}, t, vbuf(t - 1), kbuf(t));
+  };
+  auto softmax = [&](int t) {
+    page_ids(t + sd + 2);  // for the tile the next MFMA phase will load
+    const int base = t * KVT;
+    if (base + KVT > wlim_min) {
+#pragma unroll
+      for (int b = 0; b < KB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int kv = base + 32 * b + 8 * (r >> 2) + 4 * half + (r & 3);
+          if (kv >= lim) sacc[b][r] = -INFINITY;
+        }
+    }
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[b][r]);
+    mx = fmaxf(mx, other_half(mx));
+    if (__builtin_amdgcn_ballot_w64(mx > m_used + a.tau) != 0) {  // wave-uniform, rare after tile 0
+      const float m_new = fmaxf(m_used, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * a.sl2e);
+      m_used = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    const float msc = m_used * a.sl2e;
+    float lsum = 0.f;
+#pragma unroll
+    for (int b = 0; b < KB; ++b) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_fmaf(sacc[b][r], a.sl2e, -msc);
+        if (!(SP_ABLATE & 1)) p = __builtin_amdgcn_exp2f(p);
+        sacc[b][r] = p;
+        lsum += p;
+      }
+      pop[b][0] = pack8(sacc[b], 0);
+      pop[b][1] = pack8(sacc[b], 8);
+    }
+    l += lsum;
+  };
+
+  // prologue: LDS must hold K(0); the first group keeps K(1) in registers, the second V(0),
+  // and each has the page ids of its next tile in flight.
+  if (!grp) {
+    page_ids(0);
+    load_tile(0);
+    write_tile(0);
+  }
+  page_ids(sd);
+  load_tile(sd);
+  page_ids(sd + 1);  // for the first MFMA phase
+  __syncthreads();
+
+  // One barrier per key tile.  Inside a tile period the two groups run the same two phases in
+  // OPPOSITE order: the first group multiplies (PV of tile t-1, QK^T of tile t, plus its share
+  // of the staging) and then exponentiates tile t; the second group first exponentiates tile
+  // t-1 and then multiplies.  One wave of each group sits on every SIMD, so the matrix pipe and
+  // the VALU are both busy through the whole period, and since nothing forces the phase
+  // boundary to line up, a short softmax simply lets the next MFMA phase start early.
+  // Buffer hand-off: K(t+1) and V(t) are written during period t into the slots last read in
+  // period t-1, and are first read in period t+1.
+  if (grp == 0) {
+    __builtin_amdgcn_s_setprio(SP_PRIO);
+    qk(0);
+    __builtin_amdgcn_s_setprio(0);
+    softmax(0);
+    __syncthreads();
+    for (int t = 1; t < T; ++t) {
+      __builtin_amdgcn_s_setprio(SP_PRIO);
+      pv_qk(t);
+      __builtin_amdgcn_s_setprio(0);
+      softmax(t);
+      __syncthreads();
+    }
+    __builtin_amdgcn_s_setprio(SP_PRIO);
+    pv(T - 1);
+    __builtin_amdgcn_s_setprio(0);
+  } else {
+    __builtin_amdgcn_s_setprio(SP_PRIO);
+    qk(0);
+    __builtin_amdgcn_s_setprio(0);
+    __syncthreads();
+    for (int t = 1; t < T; ++t) {
+      softmax(t - 1);
+      __builtin_amdgcn_s_setprio(SP_PRIO);
+      pv_qk(t);
+      __builtin_amdgcn_s_setprio(0);
+      __syncthreads();
+    }
+    softmax(T - 1);
+    __builtin_amdgcn_s_setprio(SP_PRIO);
+    pv(T - 1);
+    __builtin_amdgcn_s_setprio(0);
+  }
+
+  // ---- normalise and store
+  float lt = l + other_half(l);
+  float inv = 1.0f / lt;
+  if (valid) {
+    char *dst = a.out + out_off;
+#pragma unroll
+    for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4)
+        store4_bf16(dst + (32 * db + 8 * r4 + 4 * half) * 2, o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv,
+                    o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv);
+  }
+}
+
+typedef void (*prefill_fn)(PrefillArgs);
+
+// Launches one prefill kernel instantiation: `cols` query columns per workgroup, `nt` threads.
+static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, int nt, const PrefillArgs &a0,
+                      int batch, int max_q_len, hipStream_t stream) {
   PrefillArgs a = a0;
-  constexpr int COLS = NW * QB * 32;
-  int tpt = COLS >> a.gshift;
+  int tpt = cols >> a.gshift;
   a.ntiles_x = (max_q_len + tpt - 1) / tpt;
-  size_t smem = 2 * (size_t)KVT * (G::kKStride + G::kVStride);
-  static bool attr_set = false;  // per instantiation; benign if two threads race
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)prefill_kernel<D, NW, QB, KVT>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (!*attr_set) {  // benign if two threads race
+    hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill smem attribute: %s", hipGetErrorString(e));
-    attr_set = true;
+    *attr_set = true;
   }
   long gy = (long)batch * a.n_hgroups;
   if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_prefill: batch * head groups = %ld exceeds 65535", gy);
-  hipLaunchKernelGGL((prefill_kernel<D, NW, QB, KVT>), dim3(a.ntiles_x, (unsigned)gy), dim3(NW * 64), smem,
-                     stream, a);
+  hipLaunchKernelGGL(fn, dim3(a.ntiles_x, (unsigned)gy), dim3(nt), smem, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill launch: %s", hipGetErrorString(e));
   return SP_OK;
 }
+
+static int g_variant = 1;      // 0 = lock-step kernel, 1 = ping-pong kernel
+static int g_interleave = 0;
+static int g_pfd = 4;
+static int g_ablate = 0;
+static long long *g_trace = nullptr;
+void set_prefill_trace(void *p) { g_trace = (long long *)p; }
+void set_prefill_ablate(int v) { g_ablate = v; }
+void set_prefill_pfd(int v) { g_pfd = v; }
+void set_prefill_variant(int v) { g_variant = v; }
+void set_prefill_interleave(int v) { g_interleave = v; }
 
 int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
@@ -294,8 +690,29 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   a.n_hgroups = num_q_heads >> gshift;
   a.ntiles_x = 0;
   a.sl2e = scale * 1.44269504088896340736f;
-  if (c.head_dim == 128) return launch_cfg<128, 8, 1, 64>(a, batch, max_q_len, stream);
-  return launch_cfg<64, 8, 1, 64>(a, batch, max_q_len, stream);
+  a.tau = 8.0f / a.sl2e;
+  a.pp_interleave = g_interleave;
+  a.ablate = g_ablate;
+  a.trace = g_trace;
+  static bool set[8] = {false, false, false, false, false, false, false, false};
+  constexpr int KVT = 64;
+  if (c.head_dim == 128) {
+    size_t smem = 2 * (size_t)KVT * (TileGeom<128>::kKStride + TileGeom<128>::kVStride);
+    if (g_variant == 0)
+      return launch_cfg(prefill_kernel<128, 8, 1, KVT>, &set[0], smem, 256, 512, a, batch, max_q_len, stream);
+    size_t smem_pp = (size_t)KVT * (2 * TileGeom<128>::kKStride + 2 * TileGeom<128>::kVStride);
+    switch (g_pfd) {
+      case 2: return launch_cfg(prefill_pp_kernel<128, KVT, 2>, &set[1], smem_pp, 256, 512, a, batch, max_q_len, stream);
+      case 6: return launch_cfg(prefill_pp_kernel<128, KVT, 6>, &set[4], smem_pp, 256, 512, a, batch, max_q_len, stream);
+      case 8: return launch_cfg(prefill_pp_kernel<128, KVT, 8>, &set[5], smem_pp, 256, 512, a, batch, max_q_len, stream);
+      default: return launch_cfg(prefill_pp_kernel<128, KVT, 4>, &set[6], smem_pp, 256, 512, a, batch, max_q_len, stream);
+    }
+  }
+  size_t smem = 2 * (size_t)KVT * (TileGeom<64>::kKStride + TileGeom<64>::kVStride);
+  if (g_variant == 0)
+    return launch_cfg(prefill_kernel<64, 8, 1, KVT>, &set[2], smem, 256, 512, a, batch, max_q_len, stream);
+  size_t smem_pp = (size_t)KVT * (2 * TileGeom<64>::kKStride + 2 * TileGeom<64>::kVStride);
+  return launch_cfg(prefill_pp_kernel<64, KVT, 4>, &set[3], smem_pp, 256, 512, a, batch, max_q_len, stream);
 }
 
 }  // namespace sp
