@@ -132,7 +132,7 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  * sp_debug_set_tuning — process-wide override of an internal launch parameter, for tuning
  * sweeps and tests.  Not thread-safe against concurrent attention calls.  Keys:
  *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a power of two in
- *                   [128, 1024].  Changes what sp_attn_decode_workspace_size returns.
+ *                   [512, 4096].  Changes what sp_attn_decode_workspace_size returns.
  * Returns SP_OK, SP_ERR_NULL or SP_ERR_UNSUPPORTED (unknown key / value out of range).
  */
 int sp_debug_set_tuning(const char *key, int32_t value);

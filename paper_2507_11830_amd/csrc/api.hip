@@ -146,35 +146,12 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
   return SP_OK;
 }
 
-// Trace builds only (-DSP_TRACE=1): device buffer of 8*128*4 int64 for per-wave timestamps.
-int sp_debug_set_trace_buffer(void *device_ptr) {
-  set_prefill_trace(device_ptr);
-  return SP_OK;
-}
-
 int sp_debug_set_tuning(const char *key, int32_t value) {
   if (!key) return fail(SP_ERR_NULL, "tuning key is NULL");
   if (!strcmp(key, "decode_chunk")) {
-    if (value != 0 && (value < 128 || value > 1024 || (value & (value - 1))))
-      return fail(SP_ERR_UNSUPPORTED, "decode_chunk=%d (0, or a power of two in [128, 1024])", value);
+    if (value != 0 && (value < 512 || value > 4096 || (value & (value - 1))))
+      return fail(SP_ERR_UNSUPPORTED, "decode_chunk=%d (0, or a power of two in [512, 4096])", value);
     set_decode_chunk(value);
-    return SP_OK;
-  }
-  if (!strcmp(key, "prefill_variant")) {
-    if (value != 0 && value != 1) return fail(SP_ERR_UNSUPPORTED, "prefill_variant=%d (0 or 1)", value);
-    set_prefill_variant(value);
-    return SP_OK;
-  }
-  if (!strcmp(key, "prefill_ablate")) {
-    set_prefill_ablate(value);
-    return SP_OK;
-  }
-  if (!strcmp(key, "prefill_pfd")) {
-    set_prefill_pfd(value);
-    return SP_OK;
-  }
-  if (!strcmp(key, "prefill_interleave")) {
-    set_prefill_interleave(value != 0);
     return SP_OK;
   }
   return fail(SP_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);

@@ -4,14 +4,15 @@
 // kernel (paper section "Introducing Shift Parallelism": the computation and data mapping of
 // attention are identical in both modes), only with one query token per sequence.
 //
-// Split kernel.  One WAVE owns one split — `chunk` consecutive keys — of one
-// (sequence, KV-head group).  The group's query heads (<= 32) are the columns of a 32-wide
-// MFMA tile, so every K/V byte is read from HBM exactly once for all heads that share it.
-// The wave walks its keys in blocks of 32 tokens (2 pages): global -> registers -> its own
-// LDS region, with the next block's loads in flight while the current block runs
-// S^T = K Q^T, the online softmax and O^T += V^T P^T.  Waves never wait for each other, so
-// the memory system sees (waves per CU) x 16 KiB in flight.  Each split writes an
-// un-normalised fp32 partial (o, m, l) per (sequence, head, split).
+// Split kernel.  One workgroup of four waves owns one split — `chunk` consecutive keys — of
+// one (sequence, KV-head group); the split is cut into four contiguous quarters, one per WAVE.
+// The group's query heads (<= 32) are the columns of a 32-wide MFMA tile, so every K/V byte is
+// read from HBM exactly once for all heads that share it.  A wave walks its keys in blocks of
+// 32 tokens (2 pages): global -> registers -> its own LDS region, with the next block's loads
+// in flight while the current block runs S^T = K Q^T, the online softmax and O^T += V^T P^T.
+// Waves never wait for each other inside the loop (no workgroup barrier), so the memory system
+// sees (waves per CU) x 16 KiB in flight.  At the end the four running states are merged
+// through LDS into one un-normalised fp32 partial (o, m, l) per (sequence, head, split).
 // Combine kernel: out = sum_k 2^(m_k - M) o_k / sum_k 2^(m_k - M) l_k in fixed split order,
 // one round-to-nearest-even to bf16.
 //
@@ -20,8 +21,9 @@
 
 namespace sp {
 
-constexpr int kDecMinChunk = 128;
-constexpr int kDecMaxChunk = 1024;  // <= 64 pages, so one lane can hold each page id of a split
+constexpr int kDecWaves = 4;
+constexpr int kDecMinChunk = 512;
+constexpr int kDecMaxChunk = 4096;  // a wave's quarter is <= 64 pages: one lane holds each page id
 
 struct DecodeArgs {
   const char *k_pages, *v_pages, *q;
@@ -36,12 +38,16 @@ static int g_chunk_override = 0;  // tuning hook (sp_debug_set_tuning), 0 = heur
 
 static int pick_chunk(int batch, int num_q_heads, int max_seq_len) {
   if (g_chunk_override > 0) return g_chunk_override;
-  // Largest chunk that still yields a few thousand splits (one wave each), assuming ~8 query
-  // heads per split and a mean length of half the maximum.  Depends only on host-side shape so
-  // the workspace size is known without reading device memory.
-  long est128 = (long)batch * ((num_q_heads + 7) / 8) * ((long)max_seq_len / 2 + 127) / 128;
-  int chunk = kDecMinChunk;
-  while (chunk < kDecMaxChunk && est128 / (2 * chunk / kDecMinChunk) >= 4096) chunk *= 2;
+  // Fewer, longer splits win as long as the grid still has on the order of a hundred
+  // workgroups: a wave's fixed costs (first loads, final merge, its partial) are amortised over
+  // more keys.  Estimate with ~8 query heads per split and a mean length of half the maximum;
+  // only host-side shape is used, so the workspace size is known without reading device memory.
+  int chunk = kDecMaxChunk;
+  while (chunk > kDecMinChunk) {
+    long est = (long)batch * ((num_q_heads + 7) / 8) * ((long)max_seq_len / 2) / chunk;
+    if (est >= 128) break;
+    chunk /= 2;
+  }
   return chunk;
 }
 
@@ -54,37 +60,44 @@ size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int h
   return (size_t)batch * num_q_heads * nsplit * (head_dim + 2) * sizeof(float);
 }
 
-// One wave per split.  No workgroup barrier anywhere: the wave stages its own 32-key blocks
-// global -> registers -> its private LDS region (next block's loads in flight during the
-// current block's MFMAs) and writes its own un-normalised partial.
+// Orders a wave's own LDS writes before its later LDS reads (and vice versa) without a
+// workgroup barrier: the hardware runs one wave's LDS operations in order, so only the
+// compiler has to be stopped from moving them across this point.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int D>
-__global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(DecodeArgs a) {
   using G = TileGeom<D>;
   constexpr int CPR = G::kChunksPerRow;
   constexpr int NCH = 32 * CPR / 64;        // 16-byte chunks per lane per matrix per block
   constexpr int ROWS_PER_LOAD = 64 / CPR;   // key rows covered by one wave-wide load
-  constexpr int KBYTES = 32 * G::kKStride, VBYTES = 32 * G::kVStride;
-  __shared__ __align__(16) char smem_raw[KBYTES + VBYTES];
-  lds_char *kb = (lds_char *)smem_raw, *vb = kb + KBYTES;
+  constexpr int KBYTES = 32 * G::kKStride, VBYTES = 32 * G::kVStride, WBYTES = KBYTES + VBYTES;
+  constexpr int OS = D + 1;                 // odd row stride of the merge buffer
+  static_assert(32 * (2 + OS) * 4 <= WBYTES, "merge state must fit the wave's tile region");
+  __shared__ __align__(16) char smem_raw[kDecWaves * WBYTES];
 
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
+  lds_char *kb = (lds_char *)smem_raw + w * WBYTES, *vb = kb + KBYTES;
   const int seq = blockIdx.y / a.n_hgroups, hg = blockIdx.y - seq * a.n_hgroups;
   const int split = blockIdx.x;
-  const int L = a.seq_lens[seq];
-  const int kv0 = split * a.chunk;
-  if (kv0 >= L) return;
-  const int kv1 = min(L, kv0 + a.chunk);
+  // A wave's quarter starts at a position that does not depend on the sequence length, so its
+  // page ids and query rows are requested in the same memory round trip as the length itself.
+  const int s0 = split * a.chunk;
+  const int per_wave = a.chunk / kDecWaves;  // a multiple of 32
+  const int kv0 = s0 + w * per_wave;
   const int head0 = hg * a.geff;
   const int kvh = head0 / a.group;
   const int ncols = min(a.geff, a.Hq - head0);  // valid columns (heads) of this tile
   const int32_t *bt_row = a.block_table + (long)seq * a.max_pages;
-
-  // Page ids of the whole split, one per lane (chunk <= 64 pages); later broadcast by readlane.
-  const int npages = (kv1 - kv0 + kPage - 1) >> 4;
-  int my_page = lane < npages ? bt_row[(kv0 >> 4) + lane] : -1;
-  if (my_page >= a.num_pages) my_page = -1;  // bad metadata must not become a wild load
-
+  // Page ids of the wave's keys, one per lane (<= 64 pages); later broadcast by readlane.
+  // Entries past the sequence end are fetched too (index clamped to the table) and never used.
+  int my_page = bt_row[min((kv0 >> 4) + lane, a.max_pages - 1)];
   bf16x8 qreg[G::kDSteps];
   {
     const char *qrow = a.q + ((long)seq * a.Hq + head0 + col) * (D * 2);
@@ -98,6 +111,11 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
       }
     }
   }
+  const int L = a.seq_lens[seq];
+  if (s0 >= L) return;  // whole workgroup
+  const int kv1 = min(min(L, s0 + a.chunk), kv0 + per_wave);
+  if (my_page >= a.num_pages) my_page = -1;  // bad metadata must not become a wild load
+
   f32x16 o[G::kDBlocks];
 #pragma unroll
   for (int db = 0; db < G::kDBlocks; ++db)
@@ -105,98 +123,143 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  u32x4 kreg[NCH], vreg[NCH];
-  auto issue_loads = [&](int base) {
+  if (kv0 < kv1) {
+    u32x4 kreg[NCH], vreg[NCH];
+    // Blocks that lie fully inside the range are loaded without any branch (a conditional load
+    // forces a full vmcnt(0) at the join, which would expose a memory round trip per block);
+    // only the last, partial block takes the guarded path that zero-fills rows past the end, so
+    // zero weights never meet NaN payloads of unwritten cache slots.
+    auto issue_loads = [&](int base) {
+      const int pslot = (base - kv0) >> 4;
+      if (base + 32 <= kv1) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int id = lane + i * 64;
-      int row = id / CPR, cc = id % CPR;
-      int kvpos = base + row;
-      // all lanes of load i sit in one page: its id comes from the lane that fetched it
-      int pg = __builtin_amdgcn_readlane(my_page, ((base - kv0) >> 4) + (i * ROWS_PER_LOAD) / kPage);
-      if (pg >= 0 && kvpos < kv1) {
-        long off = (((long)pg * a.Hkv + kvh) * kPage + (kvpos & 15)) * (D * 2) + cc * 16;
-        kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.k_pages + off));
-        vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.v_pages + off));
-      } else {  // past the split end: zeros, so zero weights never meet NaN payloads
-        kreg[i] = (u32x4){0, 0, 0, 0};
-        vreg[i] = (u32x4){0, 0, 0, 0};
+        for (int i = 0; i < NCH; ++i) {
+          int id = lane + i * 64;
+          int row = id / CPR, cc = id % CPR;
+          // all lanes of load i sit in one page: its id comes from the lane that fetched it
+          int pg = max(__builtin_amdgcn_readlane(my_page, pslot + (i * ROWS_PER_LOAD) / kPage), 0);
+          long off = (((long)pg * a.Hkv + kvh) * kPage + ((base + row) & 15)) * (D * 2) + cc * 16;
+          kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.k_pages + off));
+          vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.v_pages + off));
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+          int id = lane + i * 64;
+          int row = id / CPR, cc = id % CPR;
+          int kvpos = base + row;
+          int pg = __builtin_amdgcn_readlane(my_page, pslot + (i * ROWS_PER_LOAD) / kPage);
+          if (pg >= 0 && kvpos < kv1) {
+            long off = (((long)pg * a.Hkv + kvh) * kPage + (kvpos & 15)) * (D * 2) + cc * 16;
+            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.k_pages + off));
+            vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.v_pages + off));
+          } else {
+            kreg[i] = (u32x4){0, 0, 0, 0};
+            vreg[i] = (u32x4){0, 0, 0, 0};
+          }
+        }
       }
-    }
-  };
-  auto write_lds = [&]() {
+    };
+    auto write_lds = [&]() {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int id = lane + i * 64;
-      int row = id / CPR, cc = id % CPR;
-      *(lds_u32x4 *)(kb + row * G::kKStride + cc * 16) = kreg[i];
-      *(lds_u32x4 *)(vb + row * G::kVStride + cc * 16) = vreg[i];
-    }
-  };
+      for (int i = 0; i < NCH; ++i) {
+        int id = lane + i * 64;
+        int row = id / CPR, cc = id % CPR;
+        *(lds_u32x4 *)(kb + row * G::kKStride + cc * 16) = kreg[i];
+        *(lds_u32x4 *)(vb + row * G::kVStride + cc * 16) = vreg[i];
+      }
+    };
 
-  issue_loads(kv0);
-  for (int base = kv0; base < kv1; base += 32) {
-    write_lds();
-    __syncthreads();  // single-wave workgroup: orders the LDS writes before the reads, no s_barrier wait
-    if (base + 32 < kv1) issue_loads(base + 32);
-    f32x16 sacc;
+    issue_loads(kv0);
+    for (int base = kv0; base < kv1; base += 32) {
+      write_lds();
+      wave_lds_fence();
+      if (base + 32 < kv1) issue_loads(base + 32);
+      f32x16 sacc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < G::kDSteps; ++s) {
-      bf16x8 kop = lds_read_k_operand(kb, G::kKStride, col, 2 * s + half);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[s], sacc, 0, 0, 0);
-    }
-    if (base + 32 > kv1) {
+      for (int s = 0; s < G::kDSteps; ++s) {
+        bf16x8 kop = lds_read_k_operand(kb, G::kKStride, col, 2 * s + half);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[s], sacc, 0, 0, 0);
+      }
+      if (base + 32 > kv1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
+          if (kv >= kv1) sacc[r] = -INFINITY;
+        }
+      }
+      float mx = sacc[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+      mx = fmaxf(mx, other_half(mx));
+      const float m_new = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * a.sl2e);
+      const float msc = m_new * a.sl2e;
+      float lsum = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (kv >= kv1) sacc[r] = -INFINITY;
+        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], a.sl2e, -msc));
+        sacc[r] = p;
+        lsum += p;
       }
+      l = l * alpha + lsum;
+      m = m_new;
+      bf16x8 pop[2] = {pack8(sacc, 0), pack8(sacc, 8)};
+#pragma unroll
+      for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int db = 0; db < G::kDBlocks; ++db) {
+          bf16x8 vop = lds_read_vt_operand(vb, G::kVStride, 16 * ks + 4 * half, 32 * db, lane);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
+        }
+      wave_lds_fence();  // reads of this block done before the next block overwrites the region
     }
-    float mx = sacc[0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-    mx = fmaxf(mx, other_half(mx));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * a.sl2e);
-    const float msc = m_new * a.sl2e;
-    float lsum = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], a.sl2e, -msc));
-      sacc[r] = p;
-      lsum += p;
-    }
-    l = l * alpha + lsum;
-    m = m_new;
-    bf16x8 pop[2] = {pack8(sacc, 0), pack8(sacc, 8)};
-#pragma unroll
-    for (int db = 0; db < G::kDBlocks; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int db = 0; db < G::kDBlocks; ++db) {
-        bf16x8 vop = lds_read_vt_operand(vb, G::kVStride, 16 * ks + 4 * half, 32 * db, lane);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
-      }
-    __syncthreads();  // reads of this block done before the next block overwrites the region
   }
 
-  // ---- the split's un-normalised partial: a lane holds 4-channel runs of its column
+  // ---- merge the four waves' running states through LDS (each wave reuses its own region)
+  // layout per wave: ml[col][2] floats, then ow[col][OS] floats
   l += other_half(l);
-  if (col < ncols) {
-    long pidx = ((long)seq * a.Hq + head0 + col) * a.nsplit + split;
-    float *po = a.part_o + pidx * D;
+  {
+    lds_float *ml = (lds_float *)kb;
+    lds_float *ow = ml + 32 * 2;
+    if (col < ncols) {
+      if (half == 0) {
+        ml[col * 2 + 0] = m * a.sl2e;  // log2 units; -inf if the wave had no key
+        ml[col * 2 + 1] = l;
+      }
 #pragma unroll
-    for (int db = 0; db < G::kDBlocks; ++db)
+      for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-        *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * r4 + 4 * half) =
-            (f32x4){o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
-    if (half == 0) *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){m * a.sl2e, l};
+        for (int r = 0; r < 16; ++r) ow[col * OS + 32 * db + 8 * (r >> 2) + 4 * half + (r & 3)] = o[db][r];
+    }
+  }
+  __syncthreads();
+  // thread -> (column, channel); fixed wave order keeps the sum reproducible
+  for (int idx = tid; idx < ncols * D; idx += kDecWaves * 64) {
+    const int c = idx / D, ch = idx - c * D;
+    float mw[kDecWaves], M = -INFINITY;
+#pragma unroll
+    for (int ww = 0; ww < kDecWaves; ++ww) {
+      mw[ww] = ((lds_float *)((lds_char *)smem_raw + ww * WBYTES))[c * 2];
+      M = fmaxf(M, mw[ww]);
+    }
+    float acc = 0.f, lt = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < kDecWaves; ++ww) {
+      lds_float *wml = (lds_float *)((lds_char *)smem_raw + ww * WBYTES);
+      float f = __builtin_amdgcn_exp2f(mw[ww] - M);  // wave 0 always has a key, so M is finite
+      acc += f * wml[64 + c * OS + ch];
+      lt += f * wml[c * 2 + 1];
+    }
+    const long pidx = ((long)seq * a.Hq + head0 + c) * a.nsplit + split;
+    a.part_o[pidx * D + ch] = acc;
+    if (ch == 0) *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){M, lt};
   }
 }
 
@@ -251,17 +314,16 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float *__restr
       den += f * v[1];
     }
     int k = 0;
-    for (; k + 4 <= cnt; k += 4) {
-      f32x2 v0 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k) * D);
-      f32x2 v1 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k + 1) * D);
-      f32x2 v2 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k + 2) * D);
-      f32x2 v3 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k + 3) * D);
-      float f0 = lane_bcast(f, k), f1 = lane_bcast(f, k + 1);
-      float f2 = lane_bcast(f, k + 2), f3 = lane_bcast(f, k + 3);
-      a0 += f0 * v0[0]; a1 += f0 * v0[1];
-      a0 += f1 * v1[0]; a1 += f1 * v1[1];
-      a0 += f2 * v2[0]; a1 += f2 * v2[1];
-      a0 += f3 * v3[0]; a1 += f3 * v3[1];
+    for (; k + 8 <= cnt; k += 8) {  // eight independent loads in flight per lane
+      f32x2 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x2 *>(po + (long)(base + k + u) * D);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        float fu = lane_bcast(f, k + u);
+        a0 += fu * v[u][0];
+        a1 += fu * v[u][1];
+      }
     }
     for (; k < cnt; ++k) {
       f32x2 v0 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k) * D);
@@ -278,7 +340,7 @@ template <int D>
 static int launch_decode_d(DecodeArgs &a, char *out, int batch, hipStream_t stream) {
   long gy = (long)batch * a.n_hgroups;
   if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_decode: batch * head groups = %ld exceeds 65535", gy);
-  hipLaunchKernelGGL(decode_split_kernel<D>, dim3(a.nsplit, (unsigned)gy), dim3(64), 0, stream, a);
+  hipLaunchKernelGGL(decode_split_kernel<D>, dim3(a.nsplit, (unsigned)gy), dim3(kDecWaves * 64), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "decode split launch: %s", hipGetErrorString(e));
   hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o, a.part_ml,

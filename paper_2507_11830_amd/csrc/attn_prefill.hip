@@ -4,43 +4,22 @@
 // Per the paper's section "Introducing Shift Parallelism" this computation and its data
 // mapping are the same in both parallel modes; only the query count per sequence differs.
 //
-// Decomposition.  One workgroup owns a tile of NW*QB*32 query COLUMNS of one
+// Decomposition.  One workgroup (8 waves) owns a tile of 256 query COLUMNS of one
 // (sequence, KV head).  The G = Hq/Hkv query heads that share the KV head are stacked into the
 // column dimension (column = token * G + head), so a K/V tile staged in LDS is reused by all
-// G heads and all columns of a wave have nearly the same causal bound.  Each wave owns QB
-// blocks of 32 columns; the workgroup walks the visible keys in tiles of KVT tokens
-// (KVT/16 pages, looked up in the block table), double-buffered in LDS with the next tile's
-// global loads in flight during the current tile's MFMAs.
+// G heads and all columns of a wave have nearly the same causal bound.  Each wave owns 32
+// columns; the workgroup walks the visible keys in tiles of KVT tokens (KVT/16 pages, looked
+// up in the block table), double-buffered in LDS.
 //
 // Bound: bf16 MFMA (4 * head_dim flops per visible (query, key) pair per head).  K/V HBM
-// traffic is ~1/(8*columns) of that in bytes and is served mostly from L2.
+// traffic is ~1/(8*columns) of that in bytes and is served mostly from L2.  The resources
+// that actually run out first on gfx950 are the VALU issue port (softmax: ~4 VALU ops per
+// score, the exponential at half rate, against one MFMA per 32 scores) and LDS bandwidth
+// (every MFMA takes one 1 KiB operand from LDS), which is what the structure below is
+// organised around.
 #include <type_traits>
 
 #include "attn_tile.h"
-
-// Compile-time switches for timing experiments (results become wrong when non-zero):
-// 1 no exp, 2 no PV MFMAs, 4 no QK MFMAs, 8 no tile staging, 16 no softmax.
-#ifndef SP_ABLATE
-#define SP_ABLATE 0
-#endif
-#ifndef SP_TRACE
-#define SP_TRACE 0
-#endif
-#ifndef SP_STAGE_SGB
-#define SP_STAGE_SGB 1
-#endif
-#ifndef SP_PRIO
-#define SP_PRIO 3
-#endif
-#if SP_TRACE
-#define SP_STAMP(slot)                                                                       \
-  do {                                                                                       \
-    if (a.trace && blockIdx.x == 8 && blockIdx.y == 0 && lane == 0 && h < 128)              \
-      a.trace[(w * 128 + h) * 4 + (slot)] = __builtin_readcyclecounter();                    \
-  } while (0)
-#else
-#define SP_STAMP(slot) do { } while (0)
-#endif
 
 namespace sp {
 
@@ -56,10 +35,7 @@ __device__ __forceinline__ void sgb_prologue() {
     sgb_prologue<I + 1, N, I0, NPV, PFD>();
   }
 }
-// With STAGE, the tile-staging instructions that share the region are dealt out between the
-// MFMAs: a few VALU (address arithmetic) after every MFMA, one vector-memory load after every
-// second one, one LDS write after every fourth, so they issue in the shadow of the matrix pipe.
-template <int I, int N, int I0, int NPV, int PFD, bool STAGE>
+template <int I, int N, int I0, int NPV, int PFD>
 __device__ __forceinline__ void sgb_steady() {
   if constexpr (I < N) {
     if constexpr (I + PFD < N) {
@@ -67,12 +43,7 @@ __device__ __forceinline__ void sgb_steady() {
       else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    if constexpr (STAGE) {
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-      if constexpr (I % 4 == 1) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-      if constexpr (I % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-    sgb_steady<I + 1, N, I0, NPV, PFD, STAGE>();
+    sgb_steady<I + 1, N, I0, NPV, PFD>();
   }
 }
 
@@ -83,245 +54,24 @@ struct PrefillArgs {
   int max_pages, num_pages, Hq, Hkv, gshift, n_hgroups, ntiles_x;
   float sl2e;  // scale * log2(e)
   float tau;   // lazy-rescale threshold in raw score units (8 / sl2e)
-  int pp_interleave;  // ping-pong groups: 0 = waves {0-3},{4-7}; 1 = even/odd waves
-  int ablate;         // unused
-  long long *trace;   // SP_TRACE builds only: per-wave timestamps of one workgroup
 };
 
-template <int D, int NW, int QB, int KVT>
-__global__ __launch_bounds__(NW * 64) void prefill_kernel(PrefillArgs a) {
-  using G = TileGeom<D>;
-  constexpr int NT = NW * 64;
-  constexpr int COLS = NW * QB * 32;
-  constexpr int KB = KVT / 32;
-  constexpr int KBYTES = KVT * G::kKStride, VBYTES = KVT * G::kVStride, STAGE = KBYTES + VBYTES;
-  constexpr int CPR = G::kChunksPerRow;
-  constexpr int NCH = KVT * CPR / NT;
-  static_assert(KVT * CPR % NT == 0 && NCH >= 1, "tile does not divide over the workgroup");
-  extern __shared__ __align__(16) char smem_raw[];
-  lds_char *smem = (lds_char *)smem_raw;
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches on it scalar
-  const int col = lane & 31, half = lane >> 5;
-  const int seq = blockIdx.y / a.n_hgroups, hg = blockIdx.y - seq * a.n_hgroups;
-  const int tile = a.ntiles_x - 1 - (int)blockIdx.x;  // longest key ranges are dispatched first
-  const int tpt = COLS >> a.gshift;                   // tokens per tile
-  const int q0 = a.cu_q[seq];
-  const int q_len = a.cu_q[seq + 1] - q0;
-  const int tok0 = tile * tpt;
-  if (tok0 >= q_len) return;
-  const int ctx = a.ctx_lens[seq];
-  const int kv_end = ctx + min(q_len, tok0 + tpt);
-  const int kvh = (hg << a.gshift) / (a.Hq / a.Hkv);
-  const int32_t *bt_row = a.block_table + (long)seq * a.max_pages;
-  const int gmask = (1 << a.gshift) - 1;
-
-  // ---- per-column state and the resident Q^T operands
-  bf16x8 qreg[QB][G::kDSteps];
-  int lim[QB];
-  bool valid[QB];
-  long out_off[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    int C = (w * QB + qb) * 32 + col;
-    int token = tok0 + (C >> a.gshift);
-    int head = (hg << a.gshift) | (C & gmask);
-    valid[qb] = token < q_len;
-    lim[qb] = valid[qb] ? ctx + token + 1 : 1;
-    long row = ((long)(q0 + token) * a.Hq + head) * (D * 2);
-    out_off[qb] = row;
-#pragma unroll
-    for (int s = 0; s < G::kDSteps; ++s) {
-      if (valid[qb]) {
-        qreg[qb][s] = *reinterpret_cast<const bf16x8 *>(a.q + row + 32 * s + 16 * half);
-      } else {
-        u32x4 z = {0, 0, 0, 0};
-        qreg[qb][s] = *reinterpret_cast<bf16x8 *>(&z);
-      }
-    }
-  }
-  // Causal bounds of this wave's columns (wave-uniform).
-  const int wtok_first = tok0 + ((w * QB * 32) >> a.gshift);
-  const int wtok_last = tok0 + (((w + 1) * QB * 32 - 1) >> a.gshift);
-  const int wlim_max = wtok_first < q_len ? ctx + min(wtok_last, q_len - 1) + 1 : 0;
-  const int wlim_min = wtok_last < q_len ? ctx + wtok_first + 1 : 1;
-
-  f32x16 o[QB][G::kDBlocks];
-  float m[QB], l[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m[qb] = -INFINITY;
-    l[qb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < G::kDBlocks; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
-  }
-
-  // ---- cooperative K/V tile staging: global -> registers -> LDS
-  u32x4 kreg[NCH], vreg[NCH];
-  int pg[NCH];
-  auto load_pages = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int kvpos = t * KVT + (tid + i * NT) / CPR;
-      pg[i] = kvpos < kv_end ? bt_row[kvpos >> 4] : -1;
-    }
-  };
-  auto issue_loads = [&](int t) {
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int id = tid + i * NT;
-      int kvpos = t * KVT + id / CPR, cc = id % CPR;
-      if (pg[i] >= 0 && pg[i] < a.num_pages) {
-        long off = (((long)pg[i] * a.Hkv + kvh) * kPage + (kvpos & 15)) * (D * 2) + cc * 16;
-        kreg[i] = *reinterpret_cast<const u32x4 *>(a.k_pages + off);
-        vreg[i] = *reinterpret_cast<const u32x4 *>(a.v_pages + off);
-      } else {  // rows past the sequence end: zeros, so masked weights never meet NaN payloads
-        kreg[i] = (u32x4){0, 0, 0, 0};
-        vreg[i] = (u32x4){0, 0, 0, 0};
-      }
-    }
-  };
-  auto write_lds = [&](int buf) {
-    lds_char *kb = smem + buf * STAGE, *vb = kb + KBYTES;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      int id = tid + i * NT;
-      int row = id / CPR, cc = id % CPR;
-      *(lds_u32x4 *)(kb + row * G::kKStride + cc * 16) = kreg[i];
-      *(lds_u32x4 *)(vb + row * G::kVStride + cc * 16) = vreg[i];
-    }
-  };
-
-  const int ntiles = (kv_end + KVT - 1) / KVT;
-  load_pages(0);
-  issue_loads(0);
-  if (ntiles > 1) load_pages(1);
-  write_lds(0);
-  __syncthreads();
-
-  for (int t = 0; t < ntiles; ++t) {
-    const bool more = t + 1 < ntiles;
-    if (more) {
-      issue_loads(t + 1);
-      if (t + 2 < ntiles) load_pages(t + 2);
-    }
-    const int base = t * KVT;
-    if (base < wlim_max) {
-      const lds_char *kb = smem + (t & 1) * STAGE, *vb = kb + KBYTES;
-      // ---- S^T = K Q^T
-      f32x16 sacc[QB][KB];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int b = 0; b < KB; ++b)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[qb][b][r] = 0.f;
-#pragma unroll
-      for (int b = 0; b < KB; ++b)
-#pragma unroll
-        for (int s = 0; s < G::kDSteps; ++s) {
-          bf16x8 kop = lds_read_k_operand(kb, G::kKStride, 32 * b + col, 2 * s + half);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[qb][s], sacc[qb][b], 0, 0, 0);
-        }
-      // ---- online softmax per column, P packed straight into the PV operand layout
-      bf16x8 pop[QB][KB][2];
-      const bool need_mask = base + KVT > wlim_min;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        if (need_mask) {
-#pragma unroll
-          for (int b = 0; b < KB; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              int kv = base + 32 * b + 8 * (r >> 2) + 4 * half + (r & 3);
-              if (kv >= lim[qb]) sacc[qb][b][r] = -INFINITY;
-            }
-        }
-        float mx = sacc[qb][0][0];
-#pragma unroll
-        for (int b = 0; b < KB; ++b)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[qb][b][r]);
-        mx = fmaxf(mx, other_half(mx));
-        const float m_new = fmaxf(m[qb], mx);
-        const float alpha = __builtin_amdgcn_exp2f((m[qb] - m_new) * a.sl2e);
-        const float msc = m_new * a.sl2e;
-        float lsum = 0.f;
-#pragma unroll
-        for (int b = 0; b < KB; ++b) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][b][r], a.sl2e, -msc));
-            sacc[qb][b][r] = p;
-            lsum += p;
-          }
-          pop[qb][b][0] = pack8(sacc[qb][b], 0);
-          pop[qb][b][1] = pack8(sacc[qb][b], 8);
-        }
-        l[qb] = l[qb] * alpha + lsum;
-        m[qb] = m_new;
-#pragma unroll
-        for (int db = 0; db < G::kDBlocks; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
-      }
-      // ---- O^T += V^T P^T
-#pragma unroll
-      for (int b = 0; b < KB; ++b)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-          for (int db = 0; db < G::kDBlocks; ++db) {
-            bf16x8 vop = lds_read_vt_operand(vb, G::kVStride, 32 * b + 16 * ks + 4 * half, 32 * db, lane);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-              o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[qb][b][ks], o[qb][db], 0, 0, 0);
-          }
-    }
-    if (more) write_lds((t + 1) & 1);
-    __syncthreads();
-  }
-
-  // ---- normalise and store: a lane holds, per d-block, 4 runs of 4 consecutive channels
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    float lt = l[qb] + other_half(l[qb]);
-    float inv = 1.0f / lt;
-    if (valid[qb]) {
-      char *dst = a.out + out_off[qb];
-#pragma unroll
-      for (int db = 0; db < G::kDBlocks; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4)
-          store4_bf16(dst + (32 * db + 8 * r4 + 4 * half) * 2, o[qb][db][4 * r4] * inv,
-                      o[qb][db][4 * r4 + 1] * inv, o[qb][db][4 * r4 + 2] * inv,
-                      o[qb][db][4 * r4 + 3] * inv);
-    }
-  }
-}
-
-// Ping-pong variant (NW = 8 waves, 32 columns per wave).  The waves form two groups of four,
-// one wave of each group per SIMD.  Time is cut into half-steps separated by workgroup
-// barriers; in every half-step one group runs its MFMA phase (PV of the previous tile, then
-// QK^T of the current one) while the other runs its softmax phase on the VALU, and they swap
-// in the next half-step.  The matrix pipe of a SIMD therefore always has a wave feeding it
-// while the other wave's exponentials run beside it — barrier-synchronised waves that all
-// do the same phase at the same time leave the MFMA pipe idle during every softmax.
+// The waves form two groups of four, one wave of each group per SIMD (waves w and w+4 share a
+// SIMD).  Inside every tile period the groups run the same two phases in opposite order: one
+// multiplies (PV of the previous tile, then QK^T of the current one) while the other runs its
+// softmax on the VALU, then they swap; one workgroup barrier per tile.  Barrier-synchronised
+// waves that all do the same phase at the same time leave the matrix pipe idle during every
+// softmax and the VALU idle during every MFMA burst.
 //
 // LDS: K[2] and V[2] tile buffers.  Tile staging (global -> registers -> LDS one round later)
 // rides in the MFMA phases; page ids are fetched one further round ahead so no load waits on
 // a block-table lookup.
 //
 // The running max is only moved when some column's tile max exceeds it by more than 2^8 in
-// the exponent (kTau); otherwise weights are taken against the stale max (bounded by 2^8,
+// the exponent (tau); otherwise weights are taken against the stale max (bounded by 2^8,
 // harmless in fp32/bf16) and the O accumulators need no rescale.
 template <int D, int KVT, int PFD>
-__global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
+__global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
   using G = TileGeom<D>;
   constexpr int NT = 512, COLS = 256, KB = KVT / 32;
   constexpr int KBYTES = KVT * G::kKStride, VBYTES = KVT * G::kVStride;
@@ -369,7 +119,6 @@ __global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
   }
   const int wtok_first = tok0 + ((w * 32) >> a.gshift);
   const int wtok_last = tok0 + (((w + 1) * 32 - 1) >> a.gshift);
-  const int wlim_max = wtok_first < q_len ? ctx + min(wtok_last, q_len - 1) + 1 : 0;
   const int wlim_min = wtok_last < q_len ? ctx + wtok_first + 1 : 1;
 
   f32x16 o[G::kDBlocks];
@@ -475,26 +224,11 @@ __global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
   auto mfma_seq = [&](auto I0c, auto I1c, auto stagec, int t, const lds_char *vb, const lds_char *kb) {
     constexpr int I0 = decltype(I0c)::value, I1 = decltype(I1c)::value, N = I1 - I0;
     constexpr bool STAGE = decltype(stagec)::value;
-    if constexpr (STAGE && !(SP_ABLATE & 8)) {  // same scheduling region as the MFMAs: issued in their shadow
+    if constexpr (STAGE) {  // same basic block as the MFMAs: issued in their shadow
       write_tile(t + sd);    // loaded one round ago
       load_tile(t + sd + 1);  // its page ids were fetched in the preceding softmax phase
     }
     bf16x8 ops[N];
-    if constexpr (SP_ABLATE & 32) {  // timing experiment: MFMAs without their LDS operand traffic
-#pragma unroll
-      for (int i = 0; i < N; ++i) do_mfma(I0 + i, qreg[i % G::kDSteps]);
-      return;
-    }
-    if constexpr (SP_ABLATE & 6) {   // timing experiment: LDS operand traffic without MFMAs
-      u32x4 sink = {0, 0, 0, 0};
-#pragma unroll
-      for (int i = 0; i < N; ++i) {
-        bf16x8 v = load_op(I0 + i, vb, kb);
-        sink ^= *reinterpret_cast<u32x4 *>(&v);
-      }
-      if (sink[0] == 0x12345u) o[0][0] += 1.f;
-      return;
-    }
 #pragma unroll
     for (int i = 0; i < PFD && i < N; ++i) ops[i] = load_op(I0 + i, vb, kb);
 #pragma unroll
@@ -503,7 +237,7 @@ __global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
       do_mfma(I0 + i, ops[i]);
     }
     sgb_prologue<0, N, I0, NPV, PFD>();
-    sgb_steady<0, N, I0, NPV, PFD, STAGE && (SP_STAGE_SGB != 0)>();
+    sgb_steady<0, N, I0, NPV, PFD>();
   };
   using std::integral_constant;
   using std::true_type;
@@ -551,8 +285,7 @@ __global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
     for (int b = 0; b < KB; ++b) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = __builtin_fmaf(sacc[b][r], a.sl2e, -msc);
-        if (!(SP_ABLATE & 1)) p = __builtin_amdgcn_exp2f(p);
+        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][r], a.sl2e, -msc));
         sacc[b][r] = p;
         lsum += p;
       }
@@ -583,35 +316,35 @@ __global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
   // Buffer hand-off: K(t+1) and V(t) are written during period t into the slots last read in
   // period t-1, and are first read in period t+1.
   if (grp == 0) {
-    __builtin_amdgcn_s_setprio(SP_PRIO);
+    __builtin_amdgcn_s_setprio(3);
     qk(0);
     __builtin_amdgcn_s_setprio(0);
     softmax(0);
     __syncthreads();
     for (int t = 1; t < T; ++t) {
-      __builtin_amdgcn_s_setprio(SP_PRIO);
+      __builtin_amdgcn_s_setprio(3);
       pv_qk(t);
       __builtin_amdgcn_s_setprio(0);
       softmax(t);
       __syncthreads();
     }
-    __builtin_amdgcn_s_setprio(SP_PRIO);
+    __builtin_amdgcn_s_setprio(3);
     pv(T - 1);
     __builtin_amdgcn_s_setprio(0);
   } else {
-    __builtin_amdgcn_s_setprio(SP_PRIO);
+    __builtin_amdgcn_s_setprio(3);
     qk(0);
     __builtin_amdgcn_s_setprio(0);
     __syncthreads();
     for (int t = 1; t < T; ++t) {
       softmax(t - 1);
-      __builtin_amdgcn_s_setprio(SP_PRIO);
+      __builtin_amdgcn_s_setprio(3);
       pv_qk(t);
       __builtin_amdgcn_s_setprio(0);
       __syncthreads();
     }
     softmax(T - 1);
-    __builtin_amdgcn_s_setprio(SP_PRIO);
+    __builtin_amdgcn_s_setprio(3);
     pv(T - 1);
     __builtin_amdgcn_s_setprio(0);
   }
@@ -632,11 +365,11 @@ __global__ __launch_bounds__(512) void prefill_pp_kernel(PrefillArgs a) {
 
 typedef void (*prefill_fn)(PrefillArgs);
 
-// Launches one prefill kernel instantiation: `cols` query columns per workgroup, `nt` threads.
-static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, int nt, const PrefillArgs &a0,
-                      int batch, int max_q_len, hipStream_t stream) {
+// Launches one prefill kernel instantiation (256 query columns per workgroup, 512 threads).
+static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, const PrefillArgs &a0, int batch,
+                      int max_q_len, hipStream_t stream) {
   PrefillArgs a = a0;
-  int tpt = cols >> a.gshift;
+  int tpt = 256 >> a.gshift;
   a.ntiles_x = (max_q_len + tpt - 1) / tpt;
   if (!*attr_set) {  // benign if two threads race
     hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -645,22 +378,11 @@ static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, int 
   }
   long gy = (long)batch * a.n_hgroups;
   if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_prefill: batch * head groups = %ld exceeds 65535", gy);
-  hipLaunchKernelGGL(fn, dim3(a.ntiles_x, (unsigned)gy), dim3(nt), smem, stream, a);
+  hipLaunchKernelGGL(fn, dim3(a.ntiles_x, (unsigned)gy), dim3(512), smem, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill launch: %s", hipGetErrorString(e));
   return SP_OK;
 }
-
-static int g_variant = 1;      // 0 = lock-step kernel, 1 = ping-pong kernel
-static int g_interleave = 0;
-static int g_pfd = 4;
-static int g_ablate = 0;
-static long long *g_trace = nullptr;
-void set_prefill_trace(void *p) { g_trace = (long long *)p; }
-void set_prefill_ablate(int v) { g_ablate = v; }
-void set_prefill_pfd(int v) { g_pfd = v; }
-void set_prefill_variant(int v) { g_variant = v; }
-void set_prefill_interleave(int v) { g_interleave = v; }
 
 int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
@@ -691,28 +413,14 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   a.ntiles_x = 0;
   a.sl2e = scale * 1.44269504088896340736f;
   a.tau = 8.0f / a.sl2e;
-  a.pp_interleave = g_interleave;
-  a.ablate = g_ablate;
-  a.trace = g_trace;
-  static bool set[8] = {false, false, false, false, false, false, false, false};
-  constexpr int KVT = 64;
+  constexpr int KVT = 64, PFD = 4;
+  static bool set128 = false, set64 = false;
   if (c.head_dim == 128) {
     size_t smem = 2 * (size_t)KVT * (TileGeom<128>::kKStride + TileGeom<128>::kVStride);
-    if (g_variant == 0)
-      return launch_cfg(prefill_kernel<128, 8, 1, KVT>, &set[0], smem, 256, 512, a, batch, max_q_len, stream);
-    size_t smem_pp = (size_t)KVT * (2 * TileGeom<128>::kKStride + 2 * TileGeom<128>::kVStride);
-    switch (g_pfd) {
-      case 2: return launch_cfg(prefill_pp_kernel<128, KVT, 2>, &set[1], smem_pp, 256, 512, a, batch, max_q_len, stream);
-      case 6: return launch_cfg(prefill_pp_kernel<128, KVT, 6>, &set[4], smem_pp, 256, 512, a, batch, max_q_len, stream);
-      case 8: return launch_cfg(prefill_pp_kernel<128, KVT, 8>, &set[5], smem_pp, 256, 512, a, batch, max_q_len, stream);
-      default: return launch_cfg(prefill_pp_kernel<128, KVT, 4>, &set[6], smem_pp, 256, 512, a, batch, max_q_len, stream);
-    }
+    return launch_cfg(prefill_kernel<128, KVT, PFD>, &set128, smem, a, batch, max_q_len, stream);
   }
   size_t smem = 2 * (size_t)KVT * (TileGeom<64>::kKStride + TileGeom<64>::kVStride);
-  if (g_variant == 0)
-    return launch_cfg(prefill_kernel<64, 8, 1, KVT>, &set[2], smem, 256, 512, a, batch, max_q_len, stream);
-  size_t smem_pp = (size_t)KVT * (2 * TileGeom<64>::kKStride + 2 * TileGeom<64>::kVStride);
-  return launch_cfg(prefill_pp_kernel<64, KVT, 4>, &set[3], smem_pp, 256, 512, a, batch, max_q_len, stream);
+  return launch_cfg(prefill_kernel<64, KVT, PFD>, &set64, smem, a, batch, max_q_len, stream);
 }
 
 }  // namespace sp

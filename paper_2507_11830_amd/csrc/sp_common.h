@@ -36,11 +36,6 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
 
 // Tuning hooks behind sp_debug_set_tuning (0 restores the built-in heuristic).
 void set_decode_chunk(int chunk);
-void set_prefill_variant(int v);
-void set_prefill_interleave(int v);
-void set_prefill_pfd(int v);
-void set_prefill_ablate(int v);
-void set_prefill_trace(void *p);
 
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);
 int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
