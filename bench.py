@@ -31,6 +31,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
+# what the same counters read for the 1 GiB copy of `--workload copy` (FETCH_SIZE x2.000,
+# WRITE_SIZE x1.000); figures and commands in profiles/pmc_hbm_traffic_and_mfma.md.
+TRAFFIC_PREFILL_C2 = int(23822.3 * 1024 * 2.0 + 16384.0 * 1024)
+TRAFFIC_DECODE_C3 = int((67874.9 + 639.5) * 1024 * 2.0 + (1241.0 + 128.0) * 1024)
 
 
 def _dev_bf16(u16):
@@ -137,7 +142,7 @@ def time_phases(fns, steps, warmup):
     return wall, per
 
 
-def cpu_baseline(w, st, budget_s=12.0):
+def cpu_baseline(w, st, budget_s=1.5):
     """The fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample of the
     prefill rows (rows drawn uniformly; work = 4*d flops per visible (query, key) pair)."""
     import oracle
@@ -162,11 +167,12 @@ def cpu_baseline(w, st, budget_s=12.0):
         return flops, time.perf_counter() - t0
 
     f, t = run(2048)                       # pilot
-    n = int(min(len(lens) * int(lens.max()) * w.Hq, max(2048, 2048 * budget_s / max(t, 1e-3))))
+    n = int(max(2048, 2048 * budget_s / max(t, 1e-3)))   # about budget_s of wall time on all cores
     f, t = run(n)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": f / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"{n} uniformly drawn (sequence, token, head) rows of the same 4x2048 prefill, fp64, {t:.1f} s"}
+            "sample": f"{n} (sequence, token, head) rows drawn uniformly with replacement from the same 4x2048 "
+                      f"prefill, fp64, {t:.1f} s wall on {cores} threads"}
 
 
 def extra_long_prefill(sp, iters=5):
@@ -226,9 +232,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true", help="skip the C5a / C5c side measurements")
-    ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5c"],
+    ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5c", "copy"],
                     help="main = the step described above; c5a / c5c = only that side workload "
-                         "(used for per-kernel profiles)")
+                         "(used for per-kernel profiles); copy = a plain 1 GiB device copy, the "
+                         "known-size kernel the HBM byte counters are calibrated against")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -244,6 +251,14 @@ def main():
     import workloads as W
 
     sp.lib()   # fail loudly if the HIP library is missing
+    if args.workload == "copy":
+        n = 1 << 30
+        src = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        _, per = time_phases([lambda: dst.copy_(src)], args.steps, 2)
+        print(json.dumps({"workload": "plain device copy", "bytes_read": n, "bytes_written": n, "ms": per[0],
+                          "GBps_read_plus_write": 2 * n / per[0] / 1e6}))
+        return
     if args.workload != "main":
         fn = extra_long_prefill if args.workload == "c5a" else extra_big_decode
         print(json.dumps(fn(sp, iters=args.steps)))
@@ -286,10 +301,10 @@ def main():
                    "algorithmic_bytes": dec.bytes},
         "kv_append_GBps": pre.append_bytes / t_app_p / 1e6,
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None, "kernel": "prefill_kernel",
+                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_PREFILL_C2, "kernel": "prefill_kernel",
                      "algorithmic_flops": pre.flops},
         "roofline_decode": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                            "frac": gbps / PEAK_HBM_GBPS, "traffic": None,
+                            "frac": gbps / PEAK_HBM_GBPS, "traffic": TRAFFIC_DECODE_C3,
                             "kernel": "decode_split_kernel + decode_combine_kernel"},
     }
     if not args.no_extras:
