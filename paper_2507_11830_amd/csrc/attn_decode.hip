@@ -218,6 +218,16 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(DecodeA
           bf16x8 vop = lds_read_vt_operand(vb, G::kVStride, 16 * ks + 4 * half, 32 * db, lane);
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
         }
+      if (L <= 64) {  // very short sequences: weights as hi + lo, so bf16 rounding of P stays out of the tolerance
+        bf16x8 plo[2] = {pack8_residual(sacc, 0, pop[0]), pack8_residual(sacc, 8, pop[1])};
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int db = 0; db < G::kDBlocks; ++db) {
+            bf16x8 vop = lds_read_vt_operand(vb, G::kVStride, 16 * ks + 4 * half, 32 * db, lane);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[ks], o[db], 0, 0, 0);
+          }
+      }
       wave_lds_fence();  // reads of this block done before the next block overwrites the region
     }
   }

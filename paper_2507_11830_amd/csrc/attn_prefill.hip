@@ -294,6 +294,25 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
     }
     l += lsum;
   };
+  // Columns whose keys all lie in tile 0 (rows with at most KVT keys) take their weights as
+  // hi + lo: a second PV pass over tile 0 with the bf16 residuals of P.  Must run after
+  // softmax(0) (sacc still holds the fp32 weights) and once V(0) is visible in LDS.
+  const bool precise0 = ctx + tok0 < KVT;  // workgroup-uniform
+  auto pv_residual0 = [&]() {
+    bf16x8 hi[KB][2];
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        hi[b][ks] = pop[b][ks];
+        pop[b][ks] = pack8_residual(sacc[b], 8 * ks, hi[b][ks]);
+      }
+    pv(0);
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) pop[b][ks] = hi[b][ks];
+  };
 
   // prologue: LDS must hold K(0); the first group keeps K(1) in registers, the second V(0),
   // and each has the page ids of its next tile in flight.
@@ -321,6 +340,7 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
     __builtin_amdgcn_s_setprio(0);
     softmax(0);
     __syncthreads();
+    if (precise0) pv_residual0();  // V(0) became visible at the barrier; sacc still holds P(0)
     for (int t = 1; t < T; ++t) {
       __builtin_amdgcn_s_setprio(3);
       pv_qk(t);
@@ -336,14 +356,15 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
     qk(0);
     __builtin_amdgcn_s_setprio(0);
     __syncthreads();
+    softmax(0);
+    if (precise0) pv_residual0();
     for (int t = 1; t < T; ++t) {
-      softmax(t - 1);
       __builtin_amdgcn_s_setprio(3);
       pv_qk(t);
       __builtin_amdgcn_s_setprio(0);
       __syncthreads();
+      softmax(t);
     }
-    softmax(T - 1);
     __builtin_amdgcn_s_setprio(3);
     pv(T - 1);
     __builtin_amdgcn_s_setprio(0);

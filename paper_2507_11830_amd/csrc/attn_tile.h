@@ -76,6 +76,28 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &p, int r0) {
   return u.v;
 }
 
+// bf16 of what pack8 rounded away: p - float(hi).  Rows with only a few keys take their
+// weights as hi + lo (two MFMA passes) so that the bf16 rounding of P does not eat into the
+// output tolerance there; long rows average that rounding out and use hi alone.
+__device__ __forceinline__ bf16x8 pack8_residual(const f32x16 &p, int r0, bf16x8 hi) {
+  union {
+    bf16x8 v;
+    unsigned short s[8];
+  } h;
+  h.v = hi;
+  union {
+    bf16x2 q[4];
+    bf16x8 v;
+  } u;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float e0 = p[r0 + 2 * i] - __uint_as_float((uint32_t)h.s[2 * i] << 16);
+    float e1 = p[r0 + 2 * i + 1] - __uint_as_float((uint32_t)h.s[2 * i + 1] << 16);
+    u.q[i] = __builtin_convertvector((f32x2){e0, e1}, bf16x2);
+  }
+  return u.v;
+}
+
 // One 64-bit store of 4 consecutive bf16 outputs.
 __device__ __forceinline__ void store4_bf16(void *dst, float a, float b, float c, float d) {
   union {

@@ -93,6 +93,23 @@ def test_decode_small_ragged(Hq, Hkv, d):
     run_full_compare(custom_workload(f"decode-{Hq}-{Hkv}-{d}", lens, lens - 1, Hq, Hkv, d, "decode", seed=31))
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(16, 2), (32, 4), (64, 8)])
+def test_other_shard_shapes_of_the_sp_tp_family(Hq, Hkv):
+    """Shards of an SP x TP = P factorisation with fewer GPUs hold several KV heads each; the same
+    cache layout and kernels serve them (prefill with prefix, then a decode step)."""
+    lens = np.array([200, 77, 513])
+    run_full_compare(custom_workload(f"shape-p-{Hq}-{Hkv}", lens, [64, 0, 300], Hq, Hkv, 128, "prefill", seed=51))
+    run_full_compare(custom_workload(f"shape-d-{Hq}-{Hkv}", lens, lens - 1, Hq, Hkv, 128, "decode", seed=52))
+
+
+def test_short_query_chunks_on_long_prefixes():
+    """Speculative-verification shape: 2-8 query tokens per sequence against a long cached prefix,
+    causal inside the chunk, served by sp_attn_prefill on the same cache."""
+    new = np.array([4, 8, 2, 5, 1, 3])
+    ctx = np.array([1000, 37, 4095, 512, 16, 0])
+    run_full_compare(custom_workload("spec-verify", ctx + new, ctx, 8, 1, 128, "prefill", seed=53))
+
+
 def test_decode_with_empty_sequences():
     import torch
     import paper_2507_11830_amd as sp
