@@ -133,6 +133,10 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  * sweeps and tests.  Not thread-safe against concurrent attention calls.  Keys:
  *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a power of two in
  *                   [512, 4096].  Changes what sp_attn_decode_workspace_size returns.
+ *   "prefill_split" how a prefill workgroup's two wave groups divide the work: 0 (built-in
+ *                   heuristic on the grid size), 1 (neighbouring query columns, shared key
+ *                   tiles), 2 (same query columns, alternate key tiles, merged at the end).
+ *                   Both give the same result up to fp32 summation order.
  * Returns SP_OK, SP_ERR_NULL or SP_ERR_UNSUPPORTED (unknown key / value out of range).
  */
 int sp_debug_set_tuning(const char *key, int32_t value);

@@ -154,6 +154,11 @@ int sp_debug_set_tuning(const char *key, int32_t value) {
     set_decode_chunk(value);
     return SP_OK;
   }
+  if (!strcmp(key, "prefill_split")) {
+    if (value < 0 || value > 2) return fail(SP_ERR_UNSUPPORTED, "prefill_split=%d (0, 1 or 2)", value);
+    set_prefill_split(value);
+    return SP_OK;
+  }
   return fail(SP_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
 }
 

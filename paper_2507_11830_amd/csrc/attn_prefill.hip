@@ -70,25 +70,38 @@ struct PrefillArgs {
 // The running max is only moved when some column's tile max exceeds it by more than 2^8 in
 // the exponent (tau); otherwise weights are taken against the stale max (bounded by 2^8,
 // harmless in fp32/bf16) and the O accumulators need no rescale.
-template <int D, int KVT, int PFD>
-__global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
+//
+// SPLIT = false is the arrangement described above: the groups own neighbouring sets of 128
+// columns and share every K/V tile.  SPLIT = true is for small grids, where a few hundred
+// workgroups with a triangular causal profile leave most CUs waiting for the one with the
+// longest key range: both groups then own the SAME 128 columns and take alternate key tiles
+// (group g the tiles 2i + g, each staging its own K and V stream into its own LDS region), so
+// the critical path of the longest work item halves while the ping-pong stays intact; the two
+// running states are merged through LDS at the end like the splits of the decode path.
+template <int D, int KVT, int PFD, bool SPLIT>
+__global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   using G = TileGeom<D>;
-  constexpr int NT = 512, COLS = 256, KB = KVT / 32;
+  constexpr int NT = 512, COLS = SPLIT ? 128 : 256, KB = KVT / 32;
   constexpr int KBYTES = KVT * G::kKStride, VBYTES = KVT * G::kVStride;
   constexpr int CPR = G::kChunksPerRow;
   constexpr int NCH = KVT * CPR / NT;
   static_assert(KVT * CPR % NT == 0 && NCH >= 1, "tile does not divide over the workgroup");
   extern __shared__ __align__(16) char smem_raw[];
   lds_char *smem = (lds_char *)smem_raw;
-  auto kbuf = [&](int t) { return smem + (t & 1) * KBYTES; };
-  auto vbuf = [&](int t) { return smem + 2 * KBYTES + (t & 1) * VBYTES; };
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches on it scalar
   const int col = lane & 31, half = lane >> 5;
   const int grp = w >> 2;  // wave-uniform; waves w and w+4 share a SIMD: one wave of each group per SIMD
-  const int seq = blockIdx.y / a.n_hgroups, hg = blockIdx.y - seq * a.n_hgroups;
-  const int tile = a.ntiles_x - 1 - (int)blockIdx.x;  // longest key ranges are dispatched first
+  // Tile buffers, indexed by the group's LOCAL tile number i (SPLIT: every group has its own set)
+  lds_char *const smem_g = smem + (SPLIT ? grp * 2 * (KBYTES + VBYTES) : 0);
+  auto kbuf = [&](int i) { return smem_g + (i & 1) * KBYTES; };
+  auto vbuf = [&](int i) { return smem_g + 2 * KBYTES + (i & 1) * VBYTES; };
+  auto gtile = [&](int i) { return SPLIT ? 2 * i + grp : i; };  // local tile number -> key tile of the sequence
+  // Workgroups are dispatched in blockIdx.x-major order: the longest key ranges of ALL sequences
+  // go first, the short ones fill in behind them.
+  const int seq = blockIdx.x / a.n_hgroups, hg = blockIdx.x - seq * a.n_hgroups;
+  const int tile = a.ntiles_x - 1 - (int)blockIdx.y;
   const int tpt = COLS >> a.gshift;
   const int q0 = a.cu_q[seq];
   const int q_len = a.cu_q[seq + 1] - q0;
@@ -102,7 +115,8 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
 
   // ---- this lane's column and the resident Q^T operands
   bf16x8 qreg[G::kDSteps];
-  const int C = w * 32 + col;
+  const int wc = SPLIT ? (w & 3) : w;  // wave's 32-column block inside the workgroup's columns
+  const int C = wc * 32 + col;
   const int token = tok0 + (C >> a.gshift);
   const int head = (hg << a.gshift) | (C & gmask);
   const bool valid = token < q_len;
@@ -117,8 +131,8 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
       qreg[s] = *reinterpret_cast<bf16x8 *>(&z);
     }
   }
-  const int wtok_first = tok0 + ((w * 32) >> a.gshift);
-  const int wtok_last = tok0 + (((w + 1) * 32 - 1) >> a.gshift);
+  const int wtok_first = tok0 + ((wc * 32) >> a.gshift);
+  const int wtok_last = tok0 + (((wc + 1) * 32 - 1) >> a.gshift);
   const int wlim_min = wtok_last < q_len ? ctx + wtok_first + 1 : 1;
 
   f32x16 o[G::kDBlocks];
@@ -126,16 +140,22 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
   for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m_used = -INFINITY, l = 0.f;
+  // A column of the second SPLIT group may see only masked keys in its first tiles, or none at
+  // all: its running max starts at a large finite value so that "all masked" gives weights
+  // exp2(-inf) = 0 instead of exp2(-inf + inf).  Tile 0 always holds a visible key otherwise.
+  float m_used = SPLIT ? -1e30f : -INFINITY, l = 0.f;
   f32x16 sacc[KB];
   bf16x8 pop[KB][2];
 
-  const int T = (kv_end + KVT - 1) / KVT;  // key tiles this workgroup walks
-  const int sd = 1 - grp;  // tile offset of a group's staging: K one tile ahead, V for the current tile
+  const int T = (kv_end + KVT - 1) / KVT;           // key tiles this workgroup walks
+  const int Tl = SPLIT ? (T - grp + 1) / 2 : T;      // ... of which this group computes on
+  const int P = SPLIT ? (T + 1) / 2 : T;             // tile periods (= barriers) of the workgroup
 
-  // ---- staging, split by group: the first group moves the K tiles, the second the V tiles,
-  // each during its own MFMA phase, where the wave mostly waits on the matrix pipe and has issue
-  // slots to spare (the softmax phase has none).  Each thread handles NCH2 16-byte chunks.
+  // ---- staging.  With two groups the first moves the K tiles and the second the V tiles, each
+  // during its own MFMA phase, where the wave mostly waits on the matrix pipe and has issue
+  // slots to spare (the softmax phase has none); a single group moves both (NM = 2 matrices
+  // per thread).  K is staged one tile ahead (offset 1), V for the current tile (offset 0).
+  // Each thread handles NCH2 16-byte chunks per matrix.
   // Staging is branch-free: a conditional load leaves the waitcnt pass no choice but a full
   // vmcnt(0) at the join.  Rows past the end of the sequence are redirected to its last valid
   // row (finite data; their weights are masked to zero), tiles past the last one to the last.
@@ -143,18 +163,28 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
   // same row-of-page and column for every i: the page ids are wave-uniform (fetched with scalar
   // loads during the softmax phase, which has no LDS traffic to disturb) and the per-tile
   // vector arithmetic is three or four ops per chunk.
+  constexpr int NM = SPLIT ? 2 : 1;          // matrices this thread stages
   constexpr int NCH2 = KVT * CPR / 256;
   constexpr int RPC = 256 / CPR;             // tile rows between two chunks of one thread
   static_assert(64 / CPR <= kPage, "the rows one wave stages must lie in one page");
-  u32x4 sreg[NCH2];
-  int spg[NCH2];                             // page ids of the tile to load next (SGPRs)
+  u32x4 sreg[NM][NCH2];
+  int spg[NM][NCH2];                         // page ids of the tile to load next (SGPRs)
   const int last_kv = kv_end - 1, last_page = last_kv >> 4;
-  const int gt = tid & 255;                  // thread index inside the group (waves 0-3 / 4-7)
+  const int gt = tid & 255;                  // thread index inside the group
   const int st_row0 = gt / CPR;              // row of chunk 0 inside the tile
   const int st_wrow0 = __builtin_amdgcn_readfirstlane(st_row0);  // a wave's rows share one page
-  const char *st_col = (grp ? a.v_pages : a.k_pages) + kvh * (kPage * D * 2) + (gt % CPR) * 16;
-  const int sstride = grp ? G::kVStride : G::kKStride;
-  const int st_lds0 = st_row0 * sstride + (gt % CPR) * 16;
+  // slot k of this thread stages matrix is_v[k] (0 = K, 1 = V)
+  bool is_v[NM];
+  int sd[NM], sstride[NM], st_lds0[NM];
+  const char *st_col[NM];
+#pragma unroll
+  for (int k = 0; k < NM; ++k) {
+    is_v[k] = SPLIT ? k != 0 : grp != 0;
+    sd[k] = is_v[k] ? 0 : 1;
+    sstride[k] = is_v[k] ? G::kVStride : G::kKStride;
+    st_lds0[k] = st_row0 * sstride[k] + (gt % CPR) * 16;
+    st_col[k] = (is_v[k] ? a.v_pages : a.k_pages) + kvh * (kPage * D * 2) + (gt % CPR) * 16;
+  }
   const unsigned pool_rows_per_page = (unsigned)a.Hkv * kPage;  // rows of all heads in one page
   // row-of-page of chunk i: constant, except in pages at or past the sequence's last page,
   // where it is folded back onto a written row (rows past the end only feed masked weights)
@@ -164,26 +194,37 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
     st_rop[i] = (st_row0 + i * RPC) & 15;
     st_rop_last[i] = min(st_rop[i], last_kv & 15);
   }
-  auto page_ids = [&](int t) {  // scalar loads: t and the indices are wave-uniform
-    const int tt = min(t, T - 1);
+  auto page_ids = [&](int k, int i) {  // scalar loads: i and the indices are wave-uniform
+    const int tt = min(gtile(i), T - 1);
 #pragma unroll
-    for (int i = 0; i < NCH2; ++i)
-      spg[i] = bt_row[min((tt * KVT + i * RPC + st_wrow0) >> 4, last_page)];
+    for (int c = 0; c < NCH2; ++c)
+      spg[k][c] = bt_row[min((tt * KVT + c * RPC + st_wrow0) >> 4, last_page)];
   };
-  auto load_tile = [&](int t) {
-    const int tt = min(t, T - 1);
+  auto load_tile = [&](int k, int i) {
+    const int tt = min(gtile(i), T - 1);
 #pragma unroll
-    for (int i = 0; i < NCH2; ++i) {
-      const bool tail = ((tt * KVT + i * RPC + st_wrow0) >> 4) >= last_page;  // uniform
-      const unsigned page = (unsigned)min(max(spg[i], 0), a.num_pages - 1);  // no wild loads on bad metadata
-      const unsigned rowidx = page * pool_rows_per_page + (unsigned)(tail ? st_rop_last[i] : st_rop[i]);
-      sreg[i] = *reinterpret_cast<const u32x4 *>(st_col + (size_t)rowidx * (D * 2));
+    for (int c = 0; c < NCH2; ++c) {
+      const bool tail = ((tt * KVT + c * RPC + st_wrow0) >> 4) >= last_page;  // uniform
+      const unsigned page = (unsigned)min(max(spg[k][c], 0), a.num_pages - 1);  // no wild loads on bad metadata
+      const unsigned rowidx = page * pool_rows_per_page + (unsigned)(tail ? st_rop_last[c] : st_rop[c]);
+      sreg[k][c] = *reinterpret_cast<const u32x4 *>(st_col[k] + (size_t)rowidx * (D * 2));
     }
   };
-  auto write_tile = [&](int t) {
-    lds_char *buf = (grp ? vbuf(t) : kbuf(t)) + st_lds0;
+  auto write_tile = [&](int k, int t) {
+    lds_char *buf = (is_v[k] ? vbuf(t) : kbuf(t)) + st_lds0[k];
 #pragma unroll
-    for (int i = 0; i < NCH2; ++i) *(lds_u32x4 *)(buf + i * RPC * sstride) = sreg[i];
+    for (int i = 0; i < NCH2; ++i) *(lds_u32x4 *)(buf + i * RPC * sstride[k]) = sreg[k][i];
+  };
+  auto stage_round = [&](int t) {  // in MFMA phase t: tiles loaded one round ago go to LDS, the next are requested
+#pragma unroll
+    for (int k = 0; k < NM; ++k) {
+      write_tile(k, t + sd[k]);
+      load_tile(k, t + sd[k] + 1);  // its page ids were fetched in the preceding softmax phase
+    }
+  };
+  auto fetch_page_ids = [&](int t) {  // in softmax phase t: for the tiles MFMA phase t+1 will load
+#pragma unroll
+    for (int k = 0; k < NM; ++k) page_ids(k, t + sd[k] + 2);
   };
 
   // ---- the phases of a tile, per wave.  The MFMA phases are written as "all operand reads,
@@ -225,8 +266,7 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
     constexpr int I0 = decltype(I0c)::value, I1 = decltype(I1c)::value, N = I1 - I0;
     constexpr bool STAGE = decltype(stagec)::value;
     if constexpr (STAGE) {  // same basic block as the MFMAs: issued in their shadow
-      write_tile(t + sd);    // loaded one round ago
-      load_tile(t + sd + 1);  // its page ids were fetched in the preceding softmax phase
+      stage_round(t);
     }
     bf16x8 ops[N];
 #pragma unroll
@@ -252,8 +292,8 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
     mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, true_type{}, t, vbuf(t - 1), kbuf(t));
   };
   auto softmax = [&](int t) {
-    page_ids(t + sd + 2);  // for the tile the next MFMA phase will load
-    const int base = t * KVT;
+    fetch_page_ids(t);
+    const int base = gtile(t) * KVT;
     if (base + KVT > wlim_min) {
 #pragma unroll
       for (int b = 0; b < KB; ++b)
@@ -297,33 +337,32 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
   // Columns whose keys all lie in tile 0 (rows with at most KVT keys) take their weights as
   // hi + lo: a second PV pass over tile 0 with the bf16 residuals of P.  Must run after
   // softmax(0) (sacc still holds the fp32 weights) and once V(0) is visible in LDS.
-  const bool precise0 = ctx + tok0 < KVT;  // workgroup-uniform
+  const bool precise0 = ctx + tok0 < KVT && gtile(0) == 0;  // group-uniform
   auto pv_residual0 = [&]() {
-    bf16x8 hi[KB][2];
 #pragma unroll
     for (int b = 0; b < KB; ++b)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        hi[b][ks] = pop[b][ks];
-        pop[b][ks] = pack8_residual(sacc[b], 8 * ks, hi[b][ks]);
-      }
+      for (int ks = 0; ks < 2; ++ks) pop[b][ks] = pack8_residual(sacc[b], 8 * ks, pop[b][ks]);
     pv(0);
 #pragma unroll
-    for (int b = 0; b < KB; ++b)
+    for (int b = 0; b < KB; ++b)  // back to the rounded weights (cheaper than keeping a copy live)
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) pop[b][ks] = hi[b][ks];
+      for (int ks = 0; ks < 2; ++ks) pop[b][ks] = pack8(sacc[b], 8 * ks);
   };
 
-  // prologue: LDS must hold K(0); the first group keeps K(1) in registers, the second V(0),
-  // and each has the page ids of its next tile in flight.
-  if (!grp) {
-    page_ids(0);
-    load_tile(0);
-    write_tile(0);
+  // prologue: LDS must hold K(0); K(1) and V(0) wait in registers and the page ids of the next
+  // tiles are in flight.
+#pragma unroll
+  for (int k = 0; k < NM; ++k) {
+    if (!is_v[k]) {
+      page_ids(k, 0);
+      load_tile(k, 0);
+      write_tile(k, 0);
+    }
+    page_ids(k, sd[k]);
+    load_tile(k, sd[k]);
+    page_ids(k, sd[k] + 1);  // for the first MFMA phase
   }
-  page_ids(sd);
-  load_tile(sd);
-  page_ids(sd + 1);  // for the first MFMA phase
   __syncthreads();
 
   // One barrier per key tile.  Inside a tile period the two groups run the same two phases in
@@ -334,14 +373,14 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
   // boundary to line up, a short softmax simply lets the next MFMA phase start early.
   // Buffer hand-off: K(t+1) and V(t) are written during period t into the slots last read in
   // period t-1, and are first read in period t+1.
-  if (grp == 0) {
+  if (grp == 0) {  // always has Tl == P >= 1
     __builtin_amdgcn_s_setprio(3);
     qk(0);
     __builtin_amdgcn_s_setprio(0);
     softmax(0);
     __syncthreads();
     if (precise0) pv_residual0();  // V(0) became visible at the barrier; sacc still holds P(0)
-    for (int t = 1; t < T; ++t) {
+    for (int t = 1; t < Tl; ++t) {
       __builtin_amdgcn_s_setprio(3);
       pv_qk(t);
       __builtin_amdgcn_s_setprio(0);
@@ -349,25 +388,58 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
       __syncthreads();
     }
     __builtin_amdgcn_s_setprio(3);
-    pv(T - 1);
+    pv(Tl - 1);
     __builtin_amdgcn_s_setprio(0);
-  } else {
-    __builtin_amdgcn_s_setprio(3);
-    qk(0);
-    __builtin_amdgcn_s_setprio(0);
+  } else {  // SPLIT: may have one tile less than the first group, or none
+    if (Tl > 0) {
+      __builtin_amdgcn_s_setprio(3);
+      qk(0);
+      __builtin_amdgcn_s_setprio(0);
+    }
     __syncthreads();
-    softmax(0);
-    if (precise0) pv_residual0();
-    for (int t = 1; t < T; ++t) {
+    if (Tl > 0) {
+      softmax(0);
+      if (precise0) pv_residual0();
+      for (int t = 1; t < Tl; ++t) {
+        __builtin_amdgcn_s_setprio(3);
+        pv_qk(t);
+        __builtin_amdgcn_s_setprio(0);
+        __syncthreads();
+        softmax(t);
+      }
       __builtin_amdgcn_s_setprio(3);
-      pv_qk(t);
+      pv(Tl - 1);
       __builtin_amdgcn_s_setprio(0);
-      __syncthreads();
-      softmax(t);
     }
-    __builtin_amdgcn_s_setprio(3);
-    pv(T - 1);
-    __builtin_amdgcn_s_setprio(0);
+    for (int t = max(Tl, 1); t < P; ++t) __syncthreads();  // keep the barrier count of the first group
+  }
+
+  if (SPLIT) {
+    // ---- merge the second group's running state into the first group's (same columns, same
+    // lane layout: wave w and wave w+4 hold the same (column, channel) positions).
+    constexpr int NST = 16 * G::kDBlocks + 2;  // floats of state per lane
+    static_assert(4 * 64 * NST * 4 <= 2 * (KBYTES + VBYTES), "state must fit one group's tile region");
+    lds_float *xch = (lds_float *)(smem + 2 * (KBYTES + VBYTES)) + (w & 3) * 64 + lane;  // [value][wave][lane]
+    __syncthreads();  // every wave is done reading tiles
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xch[(16 * db + r) * 256] = o[db][r];
+      xch[(NST - 2) * 256] = m_used;
+      xch[(NST - 1) * 256] = l;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+    const float m_b = xch[(NST - 2) * 256], l_b = xch[(NST - 1) * 256];
+    const float m_new = fmaxf(m_used, m_b);  // the first group always saw a key: finite
+    const float fa = __builtin_amdgcn_exp2f((m_used - m_new) * a.sl2e);
+    const float fb = __builtin_amdgcn_exp2f((m_b - m_new) * a.sl2e);  // 0 if the second group had no tile
+    l = l * fa + l_b * fb;
+#pragma unroll
+    for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[db][r] = o[db][r] * fa + xch[(16 * db + r) * 256] * fb;
   }
 
   // ---- normalise and store
@@ -384,22 +456,26 @@ __global__ __launch_bounds__(512) void prefill_kernel(PrefillArgs a) {
   }
 }
 
+static int g_split_mode = 0;
+void set_prefill_split(int mode) { g_split_mode = mode; }
+
 typedef void (*prefill_fn)(PrefillArgs);
 
-// Launches one prefill kernel instantiation (256 query columns per workgroup, 512 threads).
-static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, const PrefillArgs &a0, int batch,
+// Launches one prefill kernel instantiation with `cols` query columns per workgroup.
+static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, const PrefillArgs &a0, int batch,
                       int max_q_len, hipStream_t stream) {
   PrefillArgs a = a0;
-  int tpt = 256 >> a.gshift;
+  int tpt = cols >> a.gshift;
   a.ntiles_x = (max_q_len + tpt - 1) / tpt;
   if (!*attr_set) {  // benign if two threads race
     hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill smem attribute: %s", hipGetErrorString(e));
     *attr_set = true;
   }
-  long gy = (long)batch * a.n_hgroups;
-  if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_prefill: batch * head groups = %ld exceeds 65535", gy);
-  hipLaunchKernelGGL(fn, dim3(a.ntiles_x, (unsigned)gy), dim3(512), smem, stream, a);
+  long gx = (long)batch * a.n_hgroups;
+  if (gx > 0x7fffffffL || a.ntiles_x > 65535)
+    return fail(SP_ERR_BAD_SHAPE, "sp_attn_prefill: grid %ld x %d exceeds the launch limits", gx, a.ntiles_x);
+  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)a.ntiles_x), dim3(512), smem, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill launch: %s", hipGetErrorString(e));
   return SP_OK;
@@ -435,13 +511,23 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   a.sl2e = scale * 1.44269504088896340736f;
   a.tau = 8.0f / a.sl2e;
   constexpr int KVT = 64, PFD = 4;
-  static bool set128 = false, set64 = false;
+  static bool set[4] = {false, false, false, false};
+  // No more 256-column workgroups than CUs: let the two wave groups split the key range of 128
+  // columns instead (halves the critical path of the longest work item; measured faster up to
+  // that grid size, slower beyond it because every K/V tile is then staged for half the columns).
+  int tpt256 = 256 >> gshift;
+  long wgs256 = (long)((max_q_len + tpt256 - 1) / tpt256) * batch * a.n_hgroups;
+  const bool small_grid = g_split_mode == 0 ? wgs256 <= 256 : g_split_mode == 2;
   if (c.head_dim == 128) {
     size_t smem = 2 * (size_t)KVT * (TileGeom<128>::kKStride + TileGeom<128>::kVStride);
-    return launch_cfg(prefill_kernel<128, KVT, PFD>, &set128, smem, a, batch, max_q_len, stream);
+    if (small_grid)
+      return launch_cfg(prefill_kernel<128, KVT, PFD, true>, &set[0], 2 * smem, 128, a, batch, max_q_len, stream);
+    return launch_cfg(prefill_kernel<128, KVT, PFD, false>, &set[1], smem, 256, a, batch, max_q_len, stream);
   }
   size_t smem = 2 * (size_t)KVT * (TileGeom<64>::kKStride + TileGeom<64>::kVStride);
-  return launch_cfg(prefill_kernel<64, KVT, PFD>, &set64, smem, a, batch, max_q_len, stream);
+  if (small_grid)
+    return launch_cfg(prefill_kernel<64, KVT, PFD, true>, &set[2], 2 * smem, 128, a, batch, max_q_len, stream);
+  return launch_cfg(prefill_kernel<64, KVT, PFD, false>, &set[3], smem, 256, a, batch, max_q_len, stream);
 }
 
 }  // namespace sp

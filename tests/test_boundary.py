@@ -90,3 +90,18 @@ def test_argument_validation_needs_no_gpu(built_lib):
     # empty batches are legal no-ops
     assert L.sp_attn_prefill(ctypes.byref(d), one, one, one, one, one, 0, 1, 0, 0, 0, 8, 0.1, 1, None, 0, None) == sp.SP_OK
     assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 0, 1, 0, 8, 0.1, None, 0, None) == sp.SP_OK
+
+
+def test_tuning_keys_are_validated(built_lib):
+    import paper_2507_11830_amd as sp
+
+    L = sp.lib()
+    assert L.sp_debug_set_tuning(None, 0) == sp.SP_ERR_NULL
+    assert L.sp_debug_set_tuning(b"no_such_key", 0) == sp.SP_ERR_UNSUPPORTED
+    for v, want in [(0, sp.SP_OK), (512, sp.SP_OK), (4096, sp.SP_OK), (768, sp.SP_ERR_UNSUPPORTED),
+                    (256, sp.SP_ERR_UNSUPPORTED), (8192, sp.SP_ERR_UNSUPPORTED)]:
+        assert L.sp_debug_set_tuning(b"decode_chunk", v) == want
+    for v, want in [(1, sp.SP_OK), (2, sp.SP_OK), (3, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
+        assert L.sp_debug_set_tuning(b"prefill_split", v) == want
+    assert L.sp_debug_set_tuning(b"decode_chunk", 0) == sp.SP_OK
+    assert L.sp_debug_set_tuning(b"prefill_split", 0) == sp.SP_OK

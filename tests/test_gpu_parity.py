@@ -93,6 +93,23 @@ def test_decode_small_ragged(Hq, Hkv, d):
     run_full_compare(custom_workload(f"decode-{Hq}-{Hkv}-{d}", lens, lens - 1, Hq, Hkv, d, "decode", seed=31))
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 1, 128), (2, 1, 64), (6, 2, 128)])
+def test_prefill_both_wave_group_modes(mode, Hq, Hkv, d):
+    """The prefill kernel divides a workgroup's work over its two wave groups either by query
+    columns or by key tiles (chosen by grid size); both must meet the oracle on the same ragged
+    batch, including sequences whose second key-tile stream is empty or fully masked."""
+    lens = [1, 17, 63, 64, 65, 127, 128, 129, 300, 0, 130, 1000]
+    ctx = [0, 5, 0, 31, 64, 0, 0, 100, 111, 0, 129, 489]
+    import paper_2507_11830_amd as sp
+
+    sp.sp_debug_set_tuning("prefill_split", mode)
+    try:
+        run_full_compare(custom_workload(f"modes-{mode}-{Hq}-{Hkv}-{d}", lens, ctx, Hq, Hkv, d, "prefill", seed=61))
+    finally:
+        sp.sp_debug_set_tuning("prefill_split", 0)
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(16, 2), (32, 4), (64, 8)])
 def test_other_shard_shapes_of_the_sp_tp_family(Hq, Hkv):
     """Shards of an SP x TP = P factorisation with fewer GPUs hold several KV heads each; the same
