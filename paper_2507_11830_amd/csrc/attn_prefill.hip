@@ -63,29 +63,38 @@ struct PrefillArgs {
 // waves that all do the same phase at the same time leave the matrix pipe idle during every
 // softmax and the VALU idle during every MFMA burst.
 //
-// LDS: K[2] and V[2] tile buffers.  Tile staging (global -> registers -> LDS one round later)
-// rides in the MFMA phases; page ids are fetched one further round ahead so no load waits on
-// a block-table lookup.
+// LDS: K[2] and V[2] tile buffers in the swizzled layout of SwzTile, filled by direct
+// global -> LDS loads (no register staging, no LDS write instructions).  The loads for the
+// next K tile and the current V tile are issued right after the barrier that frees their
+// slots and are waited for right before the next barrier, so each has a full tile period to
+// land.  The load instruction is written as inline assembly: issued through the compiler
+// builtin, every later LDS read is preceded by a full vmcnt(0) wait, because the compiler
+// cannot tell the slot being filled from the slot being read.  M0 (the LDS destination) is
+// used by nothing else in this kernel.
 //
 // The running max is only moved when some column's tile max exceeds it by more than 2^8 in
 // the exponent (tau); otherwise weights are taken against the stale max (bounded by 2^8,
 // harmless in fp32/bf16) and the O accumulators need no rescale.
 //
 // SPLIT = false is the arrangement described above: the groups own neighbouring sets of 128
-// columns and share every K/V tile.  SPLIT = true is for small grids, where a few hundred
-// workgroups with a triangular causal profile leave most CUs waiting for the one with the
-// longest key range: both groups then own the SAME 128 columns and take alternate key tiles
-// (group g the tiles 2i + g, each staging its own K and V stream into its own LDS region), so
-// the critical path of the longest work item halves while the ping-pong stays intact; the two
-// running states are merged through LDS at the end like the splits of the decode path.
+// columns and share every K/V tile (the first group brings in K, the second V).  SPLIT = true
+// is for small grids, where a few hundred workgroups with a triangular causal profile leave
+// most CUs waiting for the one with the longest key range: both groups then own the SAME 128
+// columns and take alternate key tiles (group g the tiles 2i + g, each with its own K and V
+// stream in its own LDS region), so the critical path of the longest work item halves while
+// the ping-pong stays intact; the two running states are merged through LDS at the end like
+// the splits of the decode path.
 template <int D, int KVT, int PFD, bool SPLIT>
 __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   using G = TileGeom<D>;
-  constexpr int NT = 512, COLS = SPLIT ? 128 : 256, KB = KVT / 32;
-  constexpr int KBYTES = KVT * G::kKStride, VBYTES = KVT * G::kVStride;
-  constexpr int CPR = G::kChunksPerRow;
-  constexpr int NCH = KVT * CPR / NT;
-  static_assert(KVT * CPR % NT == 0 && NCH >= 1, "tile does not divide over the workgroup");
+  using Z = SwzTile<D>;
+  constexpr int COLS = SPLIT ? 128 : 256, KB = KVT / 32;
+  constexpr int ROWB = D * 2;               // bytes of one K or V row
+  constexpr int TBYTES = KVT * ROWB;        // one tile in LDS
+  constexpr int REGION = 4 * TBYTES;        // K[2] at 0 and TBYTES, V[2] at 2 and 3 TBYTES
+  constexpr int NIW = TBYTES / 1024 / 4;    // 1 KiB load instructions per wave and tile
+  static_assert(KVT == 4 * kPage, "each of a group's four waves brings in one page of a tile");
+  static_assert((TBYTES & (TBYTES - 1)) == 0, "slot toggling flips one address bit");
   extern __shared__ __align__(16) char smem_raw[];
   lds_char *smem = (lds_char *)smem_raw;
 
@@ -93,10 +102,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches on it scalar
   const int col = lane & 31, half = lane >> 5;
   const int grp = w >> 2;  // wave-uniform; waves w and w+4 share a SIMD: one wave of each group per SIMD
-  // Tile buffers, indexed by the group's LOCAL tile number i (SPLIT: every group has its own set)
-  lds_char *const smem_g = smem + (SPLIT ? grp * 2 * (KBYTES + VBYTES) : 0);
-  auto kbuf = [&](int i) { return smem_g + (i & 1) * KBYTES; };
-  auto vbuf = [&](int i) { return smem_g + 2 * KBYTES + (i & 1) * VBYTES; };
+  const int wq = w & 3;    // wave inside its group
+  const int rb = SPLIT ? grp * REGION : 0;  // this group's tile buffers
   auto gtile = [&](int i) { return SPLIT ? 2 * i + grp : i; };  // local tile number -> key tile of the sequence
   // Workgroups are dispatched in blockIdx.x-major order: the longest key ranges of ALL sequences
   // go first, the short ones fill in behind them.
@@ -115,7 +122,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 
   // ---- this lane's column and the resident Q^T operands
   bf16x8 qreg[G::kDSteps];
-  const int wc = SPLIT ? (w & 3) : w;  // wave's 32-column block inside the workgroup's columns
+  const int wc = SPLIT ? wq : w;  // wave's 32-column block inside the workgroup's columns
   const int C = wc * 32 + col;
   const int token = tok0 + (C >> a.gshift);
   const int head = (hg << a.gshift) | (C & gmask);
@@ -151,98 +158,111 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   const int Tl = SPLIT ? (T - grp + 1) / 2 : T;      // ... of which this group computes on
   const int P = SPLIT ? (T + 1) / 2 : T;             // tile periods (= barriers) of the workgroup
 
-  // ---- staging.  With two groups the first moves the K tiles and the second the V tiles, each
-  // during its own MFMA phase, where the wave mostly waits on the matrix pipe and has issue
-  // slots to spare (the softmax phase has none); a single group moves both (NM = 2 matrices
-  // per thread).  K is staged one tile ahead (offset 1), V for the current tile (offset 0).
-  // Each thread handles NCH2 16-byte chunks per matrix.
-  // Staging is branch-free: a conditional load leaves the waitcnt pass no choice but a full
-  // vmcnt(0) at the join.  Rows past the end of the sequence are redirected to its last valid
-  // row (finite data; their weights are masked to zero), tiles past the last one to the last.
-  // With 256 threads per group, chunk i of a thread always lies in page i of the tile, in the
-  // same row-of-page and column for every i: the page ids are wave-uniform (fetched with scalar
-  // loads during the softmax phase, which has no LDS traffic to disturb) and the per-tile
-  // vector arithmetic is three or four ops per chunk.
-  constexpr int NM = SPLIT ? 2 : 1;          // matrices this thread stages
-  constexpr int NCH2 = KVT * CPR / 256;
-  constexpr int RPC = 256 / CPR;             // tile rows between two chunks of one thread
-  static_assert(64 / CPR <= kPage, "the rows one wave stages must lie in one page");
-  u32x4 sreg[NM][NCH2];
-  int spg[NM][NCH2];                         // page ids of the tile to load next (SGPRs)
+  // ---- tile loads, all issued by the first group during its MFMA phase (the one phase that
+  // starts right after a barrier AND has issue slots to spare; the same instructions placed in
+  // a softmax phase measurably lengthen it).  In SPLIT mode the first group therefore also
+  // feeds the second group's private K/V stream.  Wave wq brings in page wq of every tile
+  // (16 rows = NIW instructions of 1 KiB): lane l of instruction j fills chunk slot l % 16 of
+  // line 4j + l / 16 of that page and fetches whichever global chunk the swizzle assigns to
+  // that slot.  Rows past the end of the sequence are redirected to its last valid row (finite
+  // data; their weights are masked to zero).  Page ids are wave-uniform and read from the block
+  // table one period ahead.
+  constexpr int NSTREAM = SPLIT ? 2 : 1;  // K/V tile streams of the workgroup
+  constexpr int NLD = NSTREAM * 2 * NIW;  // load instructions per wave and period
   const int last_kv = kv_end - 1, last_page = last_kv >> 4;
-  const int gt = tid & 255;                  // thread index inside the group
-  const int st_row0 = gt / CPR;              // row of chunk 0 inside the tile
-  const int st_wrow0 = __builtin_amdgcn_readfirstlane(st_row0);  // a wave's rows share one page
-  // slot k of this thread stages matrix is_v[k] (0 = K, 1 = V)
-  bool is_v[NM];
-  int sd[NM], sstride[NM], st_lds0[NM];
-  const char *st_col[NM];
-#pragma unroll
-  for (int k = 0; k < NM; ++k) {
-    is_v[k] = SPLIT ? k != 0 : grp != 0;
-    sd[k] = is_v[k] ? 0 : 1;
-    sstride[k] = is_v[k] ? G::kVStride : G::kKStride;
-    st_lds0[k] = st_row0 * sstride[k] + (gt % CPR) * 16;
-    st_col[k] = (is_v[k] ? a.v_pages : a.k_pages) + kvh * (kPage * D * 2) + (gt % CPR) * 16;
-  }
-  const unsigned pool_rows_per_page = (unsigned)a.Hkv * kPage;  // rows of all heads in one page
-  // row-of-page of chunk i: constant, except in pages at or past the sequence's last page,
-  // where it is folded back onto a written row (rows past the end only feed masked weights)
-  int st_rop[NCH2], st_rop_last[NCH2];
-#pragma unroll
-  for (int i = 0; i < NCH2; ++i) {
-    st_rop[i] = (st_row0 + i * RPC) & 15;
-    st_rop_last[i] = min(st_rop[i], last_kv & 15);
-  }
-  auto page_ids = [&](int k, int i) {  // scalar loads: i and the indices are wave-uniform
-    const int tt = min(gtile(i), T - 1);
-#pragma unroll
-    for (int c = 0; c < NCH2; ++c)
-      spg[k][c] = bt_row[min((tt * KVT + c * RPC + st_wrow0) >> 4, last_page)];
+  const int dq = lane >> 4, dslot = lane & 15;
+  auto stream_tile = [&](int g, int i) { return SPLIT ? 2 * i + g : i; };  // local tile i of stream g
+  // The inline assembly below makes the compiler treat every later load as possibly clobbered,
+  // so block-table reads are vector loads; the value stays in a VGPR until the load that needs
+  // it is issued one period later, and only then moves to an SGPR.
+  auto page_of = [&](int gt) {  // all lanes read the same entry
+    return bt_row[min(min(gt, T - 1) * (KVT / kPage) + wq, last_page)];
   };
-  auto load_tile = [&](int k, int i) {
-    const int tt = min(gtile(i), T - 1);
+  struct TileLoad {   // wave-uniform description of one page-sized load (NIW instructions)
+    const char *pb;   // start of the (page, kv head) block in the pool
+    unsigned dst0;    // LDS byte address of this wave's part of the tile slot
+    int rip_lim;      // last row of the page that may be read
+  };
+  auto dma_prep = [&](bool is_v, int g, int gt, int pg, int slot) {
+    const bool tail = min(gt, T - 1) * (KVT / kPage) + wq >= last_page;  // uniform
+    const unsigned page = (unsigned)min(max(__builtin_amdgcn_readfirstlane(pg), 0), a.num_pages - 1);  // no wild loads on bad metadata
+    TileLoad tl;
+    tl.pb = (is_v ? a.v_pages : a.k_pages) + ((size_t)page * a.Hkv + kvh) * (kPage * ROWB);
+    tl.dst0 = (unsigned)(g * REGION + (is_v ? 2 : 0) * TBYTES + slot * TBYTES + wq * (NIW * 1024));
+    tl.rip_lim = tail ? (last_kv & 15) : 15;
+    return tl;
+  };
+  auto dma_emit = [&](bool is_v, const TileLoad &tl, int j) {  // instruction j of the load
+    const int lp = 4 * j + dq;  // line inside the page
+    const int cl = dslot ^ (is_v ? Z::gv(lp) : Z::gk(lp));
+    const int rip = D == 128 ? lp : 2 * lp + (cl >> 3);
+    const int chunk = D == 128 ? cl : (cl & 7);
+    const unsigned voff = (unsigned)(min(rip, tl.rip_lim) * ROWB + chunk * 16);
+    const unsigned dst = tl.dst0 + j * 1024;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(tl.pb));
+  };
+  using std::false_type;
+  using std::integral_constant;
+  using std::true_type;
+  // The loads of period i, prepared right after the barrier that opens it: for every stream, K
+  // of local tile i+1 and V of local tile i go into the slots whose last readers finished
+  // before that barrier.  Past a stream's last tile the loads repeat its last tile into a slot
+  // nobody reads.  The NLD instructions are then emitted one at a time, spread over the MFMA
+  // sequence: issued back to back by four waves at once they queue up at the CU's one texture
+  // address unit, and since a wave issues in order, everything behind them waits too.
+  int pg_k[NSTREAM], pg_v[NSTREAM];  // page ids of the next K and V loads (kept in VGPRs)
+  TileLoad ld[NSTREAM][2];
+  auto issue_prep = [&](int i) {
 #pragma unroll
-    for (int c = 0; c < NCH2; ++c) {
-      const bool tail = ((tt * KVT + c * RPC + st_wrow0) >> 4) >= last_page;  // uniform
-      const unsigned page = (unsigned)min(max(spg[k][c], 0), a.num_pages - 1);  // no wild loads on bad metadata
-      const unsigned rowidx = page * pool_rows_per_page + (unsigned)(tail ? st_rop_last[c] : st_rop[c]);
-      sreg[k][c] = *reinterpret_cast<const u32x4 *>(st_col[k] + (size_t)rowidx * (D * 2));
+    for (int g = 0; g < NSTREAM; ++g) {
+      ld[g][0] = dma_prep(false, g, stream_tile(g, i + 1), pg_k[g], (i + 1) & 1);
+      ld[g][1] = dma_prep(true, g, stream_tile(g, i), pg_v[g], i & 1);
+      pg_v[g] = pg_k[g];
+      pg_k[g] = page_of(stream_tile(g, i + 2));
     }
   };
-  auto write_tile = [&](int k, int t) {
-    lds_char *buf = (is_v[k] ? vbuf(t) : kbuf(t)) + st_lds0[k];
-#pragma unroll
-    for (int i = 0; i < NCH2; ++i) *(lds_u32x4 *)(buf + i * RPC * sstride[k]) = sreg[k][i];
+  auto issue_emit = [&](int n) {  // n-th instruction of the period, n < NLD: streams and matrices interleaved
+    const int j = n / (2 * NSTREAM), g = (n / 2) % NSTREAM, m = n & 1;
+    dma_emit(m != 0, ld[g][m], j);
   };
-  auto stage_round = [&](int t) {  // in MFMA phase t: tiles loaded one round ago go to LDS, the next are requested
-#pragma unroll
-    for (int k = 0; k < NM; ++k) {
-      write_tile(k, t + sd[k]);
-      load_tile(k, t + sd[k] + 1);  // its page ids were fetched in the preceding softmax phase
-    }
-  };
-  auto fetch_page_ids = [&](int t) {  // in softmax phase t: for the tiles MFMA phase t+1 will load
-#pragma unroll
-    for (int k = 0; k < NM; ++k) page_ids(k, t + sd[k] + 2);
-  };
+  auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0) only
 
-  // ---- the phases of a tile, per wave.  The MFMA phases are written as "all operand reads,
-  // then all MFMAs" and pinned to an interleaved issue order with sched_group_barrier, so that
-  // LDS reads run a fixed distance ahead of the MFMAs that consume them (left alone, the
-  // scheduler places each read right before its use and the matrix pipe waits on LDS latency).
-  // PFD: how many MFMAs ahead of their use the operand reads are issued
+  // ---- LDS operand addresses of this lane (bytes from the start of LDS) for the current K slot
+  // and the current V slot; a slot change flips one address bit.
+  int kcur[G::kDSteps], vcur[G::kDBlocks];
+#pragma unroll
+  for (int s = 0; s < G::kDSteps; ++s) kcur[s] = rb + Z::template offset<false>(col, 2 * s + half);
+  {
+    const int n = lane & 15, dg = (lane >> 4) & 1;
+#pragma unroll
+    for (int db = 0; db < G::kDBlocks; ++db)
+      vcur[db] = rb + 2 * TBYTES + Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) +
+                 8 * (n & 1);
+  }
+
+  // ---- the phases of a tile, per wave.  The MFMA phases are written software-pipelined ("read
+  // operand i+PFD, MFMA i") and pinned to that issue order with sched_group_barrier, so that LDS
+  // reads run a fixed distance ahead of the MFMAs that consume them (left alone, the scheduler
+  // places each read right before its use and the matrix pipe waits on LDS latency).
   constexpr int NPV = KB * 2 * G::kDBlocks, NQK = KB * G::kDSteps;
-  // Operand i of the fused sequence "PV of tile tv, then QK^T of tile tk": i < NPV is a V^T
-  // operand (two transposing reads), the rest are K operands (one 16-byte read).
-  auto load_op = [&](int i, const lds_char *vb, const lds_char *kb) -> bf16x8 {
+  // Operand i of the fused sequence "PV of one tile, then QK^T of the next": i < NPV is a V^T
+  // operand (two transposing reads: key rows 32b + 16ks + 4*half + 0..3 and the same + 8, in the
+  // row order the score accumulator dictates), the rest are K operands (one 16-byte read).
+  auto load_op = [&](int i) -> bf16x8 {
     if (i < NPV) {
       int db = i % G::kDBlocks, ks = (i / G::kDBlocks) & 1, b = i / (2 * G::kDBlocks);
-      return lds_read_vt_operand(vb, G::kVStride, 32 * b + 16 * ks + 4 * half, 32 * db, lane);
+      const lds_char *p = smem + vcur[db] + (32 * b + 16 * ks) * ROWB;
+      union {
+        struct { s16x4 a, b; } s;
+        bf16x8 v;
+      } u;
+      u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+      u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * ROWB));
+      return u.v;
     }
     int j = i - NPV;
     int s = j % G::kDSteps, b = j / G::kDSteps;
-    return lds_read_k_operand(kb, G::kKStride, 32 * b + col, 2 * s + half);
+    return *(const lds_bf16x8 *)(smem + kcur[s] + 32 * b * ROWB);
   };
   auto do_mfma = [&](int i, bf16x8 op) {
     if (i < NPV) {
@@ -258,41 +278,46 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op, qreg[s], sacc[b], 0, 0, 0);
     }
   };
-  // Runs operands [I0, I1) software-pipelined: the source order already interleaves "read
-  // operand i+PFD, MFMA i", and sched_group_barrier pins that order through scheduling (left
-  // alone, the scheduler sinks each read to just before its use and the matrix pipe then
-  // waits a full LDS latency per MFMA pair).
-  auto mfma_seq = [&](auto I0c, auto I1c, auto stagec, int t, const lds_char *vb, const lds_char *kb) {
+  auto mfma_seq = [&](auto I0c, auto I1c, auto stagec) {
     constexpr int I0 = decltype(I0c)::value, I1 = decltype(I1c)::value, N = I1 - I0;
-    constexpr bool STAGE = decltype(stagec)::value;
-    if constexpr (STAGE) {  // same basic block as the MFMAs: issued in their shadow
-      stage_round(t);
-    }
+    constexpr bool STAGE = decltype(stagec)::value;  // emit this period's tile loads along the way
+    constexpr int GAP = N >= NLD ? N / NLD : 1, PER = N >= NLD ? 1 : NLD / N;  // loads per MFMA slot
     bf16x8 ops[N];
 #pragma unroll
-    for (int i = 0; i < PFD && i < N; ++i) ops[i] = load_op(I0 + i, vb, kb);
+    for (int i = 0; i < PFD && i < N; ++i) ops[i] = load_op(I0 + i);
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      if (i + PFD < N) ops[i + PFD] = load_op(I0 + i + PFD, vb, kb);
+      if (i + PFD < N) ops[i + PFD] = load_op(I0 + i + PFD);
       do_mfma(I0 + i, ops[i]);
+      if (STAGE && i % GAP == 0 && i / GAP * PER < NLD) {
+#pragma unroll
+        for (int e = 0; e < PER; ++e) issue_emit(i / GAP * PER + e);
+      }
     }
     sgb_prologue<0, N, I0, NPV, PFD>();
     sgb_steady<0, N, I0, NPV, PFD>();
   };
-  using std::integral_constant;
-  using std::true_type;
-  using std::false_type;
-  auto qk = [&](int t) {
-    mfma_seq(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, true_type{}, t, kbuf(t), kbuf(t));
+  auto next_k_slot = [&]() {
+#pragma unroll
+    for (int s = 0; s < G::kDSteps; ++s) kcur[s] ^= TBYTES;
   };
-  auto pv = [&](int t) {
-    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV>{}, false_type{}, t, vbuf(t), vbuf(t));
+  auto next_v_slot = [&]() {
+#pragma unroll
+    for (int db = 0; db < G::kDBlocks; ++db) vcur[db] ^= TBYTES;
   };
-  auto pv_qk = [&](int t) {
-    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, true_type{}, t, vbuf(t - 1), kbuf(t));
+  auto qk = [&](auto stagec) {  // QK^T of the tile in the current K slot
+    mfma_seq(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, stagec);
+    next_k_slot();
+  };
+  auto pv = [&]() {  // PV of the tile in the current V slot (slot kept)
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV>{}, false_type{});
+  };
+  auto pv_qk = [&](auto stagec) {  // PV of the previous tile, then QK^T of the current one
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, stagec);
+    next_k_slot();
+    next_v_slot();
   };
   auto softmax = [&](int t) {
-    fetch_page_ids(t);
     const int base = gtile(t) * KVT;
     if (base + KVT > wlim_min) {
 #pragma unroll
@@ -343,57 +368,61 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     for (int b = 0; b < KB; ++b)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) pop[b][ks] = pack8_residual(sacc[b], 8 * ks, pop[b][ks]);
-    pv(0);
+    pv();
 #pragma unroll
     for (int b = 0; b < KB; ++b)  // back to the rounded weights (cheaper than keeping a copy live)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) pop[b][ks] = pack8(sacc[b], 8 * ks);
   };
 
-  // prologue: LDS must hold K(0); K(1) and V(0) wait in registers and the page ids of the next
-  // tiles are in flight.
+  // prologue: K of every stream's first tile must be in LDS before anything is multiplied
+  if (grp == 0) {
 #pragma unroll
-  for (int k = 0; k < NM; ++k) {
-    if (!is_v[k]) {
-      page_ids(k, 0);
-      load_tile(k, 0);
-      write_tile(k, 0);
+    for (int g = 0; g < NSTREAM; ++g) {
+      TileLoad k0 = dma_prep(false, g, stream_tile(g, 0), page_of(stream_tile(g, 0)), 0);
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) dma_emit(false, k0, j);
+      pg_k[g] = page_of(stream_tile(g, 1));
+      pg_v[g] = page_of(stream_tile(g, 0));
     }
-    page_ids(k, sd[k]);
-    load_tile(k, sd[k]);
-    page_ids(k, sd[k] + 1);  // for the first MFMA phase
   }
+  wait_loads();
   __syncthreads();
 
   // One barrier per key tile.  Inside a tile period the two groups run the same two phases in
-  // OPPOSITE order: the first group multiplies (PV of tile t-1, QK^T of tile t, plus its share
-  // of the staging) and then exponentiates tile t; the second group first exponentiates tile
-  // t-1 and then multiplies.  One wave of each group sits on every SIMD, so the matrix pipe and
-  // the VALU are both busy through the whole period, and since nothing forces the phase
-  // boundary to line up, a short softmax simply lets the next MFMA phase start early.
-  // Buffer hand-off: K(t+1) and V(t) are written during period t into the slots last read in
-  // period t-1, and are first read in period t+1.
+  // OPPOSITE order: the first group multiplies (PV of tile t-1, QK^T of tile t) and then
+  // exponentiates tile t; the second group first exponentiates tile t-1 and then multiplies.
+  // One wave of each group sits on every SIMD, so the matrix pipe and the VALU are both busy
+  // through the whole period, and since nothing forces the phase boundary to line up, a short
+  // softmax simply lets the next MFMA phase start early.
+  // Buffer hand-off: K(t+1) and V(t) are requested in the first group's MFMA phase of period t
+  // into the slots last read in period t-1, have landed before the barrier that ends period t,
+  // and are first read in period t+1.
   if (grp == 0) {  // always has Tl == P >= 1
+    issue_prep(0);
     __builtin_amdgcn_s_setprio(3);
-    qk(0);
+    qk(true_type{});
     __builtin_amdgcn_s_setprio(0);
     softmax(0);
+    wait_loads();
     __syncthreads();
     if (precise0) pv_residual0();  // V(0) became visible at the barrier; sacc still holds P(0)
     for (int t = 1; t < Tl; ++t) {
+      issue_prep(t);
       __builtin_amdgcn_s_setprio(3);
-      pv_qk(t);
+      pv_qk(true_type{});
       __builtin_amdgcn_s_setprio(0);
       softmax(t);
+      wait_loads();
       __syncthreads();
     }
     __builtin_amdgcn_s_setprio(3);
-    pv(Tl - 1);
+    pv();
     __builtin_amdgcn_s_setprio(0);
   } else {  // SPLIT: may have one tile less than the first group, or none
     if (Tl > 0) {
       __builtin_amdgcn_s_setprio(3);
-      qk(0);
+      qk(false_type{});
       __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();
@@ -402,13 +431,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       if (precise0) pv_residual0();
       for (int t = 1; t < Tl; ++t) {
         __builtin_amdgcn_s_setprio(3);
-        pv_qk(t);
+        pv_qk(false_type{});
         __builtin_amdgcn_s_setprio(0);
         __syncthreads();
         softmax(t);
       }
       __builtin_amdgcn_s_setprio(3);
-      pv(Tl - 1);
+      pv();
       __builtin_amdgcn_s_setprio(0);
     }
     for (int t = max(Tl, 1); t < P; ++t) __syncthreads();  // keep the barrier count of the first group
@@ -418,8 +447,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     // ---- merge the second group's running state into the first group's (same columns, same
     // lane layout: wave w and wave w+4 hold the same (column, channel) positions).
     constexpr int NST = 16 * G::kDBlocks + 2;  // floats of state per lane
-    static_assert(4 * 64 * NST * 4 <= 2 * (KBYTES + VBYTES), "state must fit one group's tile region");
-    lds_float *xch = (lds_float *)(smem + 2 * (KBYTES + VBYTES)) + (w & 3) * 64 + lane;  // [value][wave][lane]
+    static_assert(256 * NST * 4 <= 2 * REGION, "state must fit the tile buffers");
+    lds_float *xch = (lds_float *)smem + wq * 64 + lane;  // [value][wave][lane]
     __syncthreads();  // every wave is done reading tiles
     if (grp == 1) {
 #pragma unroll
@@ -519,12 +548,12 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   long wgs256 = (long)((max_q_len + tpt256 - 1) / tpt256) * batch * a.n_hgroups;
   const bool small_grid = g_split_mode == 0 ? wgs256 <= 256 : g_split_mode == 2;
   if (c.head_dim == 128) {
-    size_t smem = 2 * (size_t)KVT * (TileGeom<128>::kKStride + TileGeom<128>::kVStride);
+    size_t smem = 4 * (size_t)KVT * 128 * 2;  // K[2] V[2], unpadded
     if (small_grid)
       return launch_cfg(prefill_kernel<128, KVT, PFD, true>, &set[0], 2 * smem, 128, a, batch, max_q_len, stream);
     return launch_cfg(prefill_kernel<128, KVT, PFD, false>, &set[1], smem, 256, a, batch, max_q_len, stream);
   }
-  size_t smem = 2 * (size_t)KVT * (TileGeom<64>::kKStride + TileGeom<64>::kVStride);
+  size_t smem = 4 * (size_t)KVT * 64 * 2;
   if (small_grid)
     return launch_cfg(prefill_kernel<64, KVT, PFD, true>, &set[2], 2 * smem, 128, a, batch, max_q_len, stream);
   return launch_cfg(prefill_kernel<64, KVT, PFD, false>, &set[3], smem, 256, a, batch, max_q_len, stream);

@@ -58,6 +58,30 @@ __device__ __forceinline__ bf16x8 lds_read_vt_operand(const lds_char *vbuf, int 
   return u.v;
 }
 
+// Swizzled, unpadded tile layout (prefill kernel).  Tiles are brought in with direct
+// global -> LDS loads, which place the 64 lanes' 16-byte chunks back to back; padding between
+// rows is therefore impossible, but every lane may fetch ANY global chunk, so the bank spread
+// comes from a permutation instead: a tile is a sequence of 256-byte lines (one row at
+// head_dim 128, two rows at 64) and chunk c of line L is stored in chunk slot c ^ g(L).
+//   K tiles, g = L mod 16 (mod 8 at head_dim 64): the 16 consecutive rows that 16 lanes of a K
+//   operand read (same chunk index) land in 16 different slots.
+//   V tiles, g = 4 * (L mod 4) (4 * (L mod 2)): the 4 rows x 4 chunks that one half-wave of a
+//   transposing V^T read touches land in 16 different slots.
+template <int D>
+struct SwzTile {
+  static_assert(D == 128 || D == 64, "head_dim");
+  static constexpr int kRowBytes = D * 2;
+  __device__ static __forceinline__ int gk(int line) { return D == 128 ? (line & 15) : (line & 7); }
+  __device__ static __forceinline__ int gv(int line) { return D == 128 ? ((line & 3) << 2) : ((line & 1) << 2); }
+  // byte offset of 16-byte chunk `chunk` of tile row `row`
+  template <bool V>
+  __device__ static __forceinline__ int offset(int row, int chunk) {
+    const int line = D == 128 ? row : row >> 1;
+    const int c = D == 128 ? chunk : (((row & 1) << 3) | chunk);
+    return line * 256 + ((c ^ (V ? gv(line) : gk(line))) << 4);
+  }
+};
+
 // Exchange between the two 32-lane halves: returns the value held by lane ^ 32.
 __device__ __forceinline__ float other_half(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
