@@ -132,7 +132,9 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  * sp_debug_set_tuning — process-wide override of an internal launch parameter, for tuning
  * sweeps and tests.  Not thread-safe against concurrent attention calls.  Keys:
  *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a power of two in
- *                   [512, 4096].  Changes what sp_attn_decode_workspace_size returns.
+ *                   [128, 1024].  Changes what sp_attn_decode_workspace_size returns.
+ *   "decode_ring"   32-key blocks a decode wave keeps in its LDS ring (one computed on, the
+ *                   rest in flight): 0 (built-in choice) or 2..4.
  *   "prefill_split" how a prefill workgroup's two wave groups divide the work: 0 (built-in
  *                   heuristic on the grid size), 1 (neighbouring query columns, shared key
  *                   tiles), 2 (same query columns, alternate key tiles, merged at the end).

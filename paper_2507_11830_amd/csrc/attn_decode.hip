@@ -4,26 +4,25 @@
 // kernel (paper section "Introducing Shift Parallelism": the computation and data mapping of
 // attention are identical in both modes), only with one query token per sequence.
 //
-// Split kernel.  One workgroup of four waves owns one split — `chunk` consecutive keys — of
-// one (sequence, KV-head group); the split is cut into four contiguous quarters, one per WAVE.
-// The group's query heads (<= 32) are the columns of a 32-wide MFMA tile, so every K/V byte is
-// read from HBM exactly once for all heads that share it.  A wave walks its keys in blocks of
-// 32 tokens (2 pages): global -> registers -> its own LDS region, with the next block's loads
-// in flight while the current block runs S^T = K Q^T, the online softmax and O^T += V^T P^T.
-// Waves never wait for each other inside the loop (no workgroup barrier), so the memory system
-// sees (waves per CU) x 16 KiB in flight.  At the end the four running states are merged
-// through LDS into one un-normalised fp32 partial (o, m, l) per (sequence, head, split).
-// Combine kernel: out = sum_k 2^(m_k - M) o_k / sum_k 2^(m_k - M) l_k in fixed split order,
-// one round-to-nearest-even to bf16.
+// Split kernel.  One WAVE (a 64-thread workgroup) owns one split — `chunk` consecutive keys —
+// of one (sequence, KV-head group).  The group's query heads (<= 32) are the columns of a
+// 32-wide MFMA tile, so every K/V byte is read from HBM exactly once for all heads that share
+// it.  The wave walks its keys in blocks of 32 tokens (2 pages) through a private ring of NB
+// LDS slots that are filled by direct global -> LDS loads: while block i runs S^T = K Q^T, the
+// online softmax and O^T += V^T P^T, the loads of blocks i+1 .. i+NB-1 are in flight.  The
+// kernel is latency-bound unless every CU has several blocks outstanding at all times, and
+// LDS (160 KiB per CU) holds far more in-flight data than registers can; nothing in the loop
+// synchronises with another wave.  Each wave writes one un-normalised fp32 partial (o, m, l)
+// per head.  Combine kernel: out = sum_k 2^(m_k - M) o_k / sum_k 2^(m_k - M) l_k in fixed
+// split order, one round-to-nearest-even to bf16.
 //
 // Bound: HBM bandwidth.  Algorithmic bytes: 4 * head_dim per cached token per KV head.
 #include "attn_tile.h"
 
 namespace sp {
 
-constexpr int kDecWaves = 4;
-constexpr int kDecMinChunk = 512;
-constexpr int kDecMaxChunk = 4096;  // a wave's quarter is <= 64 pages: one lane holds each page id
+constexpr int kDecMinChunk = 128;
+constexpr int kDecMaxChunk = 1024;  // <= 64 pages per wave: one lane holds each page id
 
 struct DecodeArgs {
   const char *k_pages, *v_pages, *q;
@@ -32,26 +31,29 @@ struct DecodeArgs {
   float *part_ml;  // [batch][Hq][nsplit][2]  (m in log2 units, l)
   int max_pages, num_pages, Hq, Hkv, group, geff, n_hgroups, chunk, nsplit;
   float sl2e;
+  float tau;  // lazy-rescale threshold in raw score units (8 / sl2e)
 };
 
-static int g_chunk_override = 0;  // tuning hook (sp_debug_set_tuning), 0 = heuristic
+static int g_chunk_override = 0;  // tuning hooks (sp_debug_set_tuning), 0 = heuristic
+static int g_ring_override = 0;
 
 static int pick_chunk(int batch, int num_q_heads, int max_seq_len) {
   if (g_chunk_override > 0) return g_chunk_override;
-  // Fewer, longer splits win as long as the grid still has on the order of a hundred
-  // workgroups: a wave's fixed costs (first loads, final merge, its partial) are amortised over
-  // more keys.  Estimate with ~8 query heads per split and a mean length of half the maximum;
-  // only host-side shape is used, so the workspace size is known without reading device memory.
+  // Longer splits amortise a wave's fixed costs (first loads, its partial, the combine pass),
+  // shorter ones fill and balance the chip: aim for a few waves per CU.  Estimate with ~8 query
+  // heads per split and a mean length of half the maximum; only host-side shape is used, so
+  // the workspace size is known without reading device memory.
   int chunk = kDecMaxChunk;
   while (chunk > kDecMinChunk) {
     long est = (long)batch * ((num_q_heads + 7) / 8) * ((long)max_seq_len / 2) / chunk;
-    if (est >= 128) break;
+    if (est >= 512) break;
     chunk /= 2;
   }
   return chunk;
 }
 
 void set_decode_chunk(int chunk) { g_chunk_override = chunk; }
+void set_decode_ring(int slots) { g_ring_override = slots; }
 
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim) {
   if (max_seq_len <= 0) return 0;
@@ -60,37 +62,36 @@ size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int h
   return (size_t)batch * num_q_heads * nsplit * (head_dim + 2) * sizeof(float);
 }
 
-// Orders a wave's own LDS writes before its later LDS reads (and vice versa) without a
-// workgroup barrier: the hardware runs one wave's LDS operations in order, so only the
-// compiler has to be stopped from moving them across this point.
-__device__ __forceinline__ void wave_lds_fence() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+// s_waitcnt that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, expcnt and lgkmcnt left at their maxima).  The "memory" clobber keeps the compiler from
+// moving LDS reads of the awaited block above it.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D>
-__global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(DecodeArgs a) {
+template <int D, int NB>
+__global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   using G = TileGeom<D>;
-  constexpr int CPR = G::kChunksPerRow;
-  constexpr int NCH = 32 * CPR / 64;        // 16-byte chunks per lane per matrix per block
-  constexpr int ROWS_PER_LOAD = 64 / CPR;   // key rows covered by one wave-wide load
-  constexpr int KBYTES = 32 * G::kKStride, VBYTES = 32 * G::kVStride, WBYTES = KBYTES + VBYTES;
-  constexpr int OS = D + 1;                 // odd row stride of the merge buffer
-  static_assert(32 * (2 + OS) * 4 <= WBYTES, "merge state must fit the wave's tile region");
-  __shared__ __align__(16) char smem_raw[kDecWaves * WBYTES];
+  using Z = SwzTile<D>;
+  constexpr int ROWB = D * 2;           // bytes of one K or V row
+  constexpr int MBYTES = 32 * ROWB;     // one 32-key block of K or of V in LDS (swizzled, unpadded)
+  constexpr int SLOT = 2 * MBYTES;      // K block, then V block
+  constexpr int NI = MBYTES / 1024;     // 1 KiB load instructions per matrix and block
+  constexpr int RPI = 1024 / ROWB;      // key rows per load instruction
+  constexpr int LPB = 2 * NI;           // load instructions per block
+  static_assert((NB - 1) * LPB < 64, "outstanding loads must fit the vmcnt counter");
+  extern __shared__ __align__(16) char smem_raw[];
+  lds_char *smem = (lds_char *)smem_raw;
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = threadIdx.x;
   const int col = lane & 31, half = lane >> 5;
-  lds_char *kb = (lds_char *)smem_raw + w * WBYTES, *vb = kb + KBYTES;
   const int seq = blockIdx.y / a.n_hgroups, hg = blockIdx.y - seq * a.n_hgroups;
   const int split = blockIdx.x;
-  // A wave's quarter starts at a position that does not depend on the sequence length, so its
-  // page ids and query rows are requested in the same memory round trip as the length itself.
-  const int s0 = split * a.chunk;
-  const int per_wave = a.chunk / kDecWaves;  // a multiple of 32
-  const int kv0 = s0 + w * per_wave;
+  // A split starts at a position that does not depend on the sequence length, so its page ids
+  // and query rows are requested in the same memory round trip as the length itself.
+  const int kv0 = split * a.chunk;  // a multiple of 32
   const int head0 = hg * a.geff;
   const int kvh = head0 / a.group;
   const int ncols = min(a.geff, a.Hq - head0);  // valid columns (heads) of this tile
@@ -112,9 +113,89 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(DecodeA
     }
   }
   const int L = a.seq_lens[seq];
-  if (s0 >= L) return;  // whole workgroup
-  const int kv1 = min(min(L, s0 + a.chunk), kv0 + per_wave);
-  if (my_page >= a.num_pages) my_page = -1;  // bad metadata must not become a wild load
+  if (kv0 >= L) {  // nothing to attend to: an empty partial, so the combine pass needs no lengths
+    if (lane < ncols)
+      *reinterpret_cast<f32x2 *>(a.part_ml + (((long)seq * a.Hq + head0 + lane) * a.nsplit + split) * 2) =
+          (f32x2){-INFINITY, 0.f};
+    return;
+  }
+  const int kv1 = min(L, kv0 + a.chunk);
+  const int nb = (kv1 - kv0 + 31) >> 5;  // blocks of this wave, >= 1
+  my_page = min(max(my_page, 0), a.num_pages - 1);  // bad metadata must not become a wild load
+
+  // ---- block loads.  Instruction j of a matrix covers RPI rows: lane l fills chunk slot l % 16
+  // of line 4j + l / 16 of the block and fetches whichever global chunk the swizzle assigns to
+  // that slot.  Rows past the end of the range are redirected to its last row (finite data;
+  // their scores are masked).
+  const int last_row = kv1 - 1 - kv0;  // relative to kv0
+  const int dq = lane >> 4, dslot = lane & 15;
+  constexpr int IPP = NI / 2;  // load instructions per page and matrix
+  unsigned voff_k[IPP], voff_v[IPP];  // this lane's byte offset inside a (page, kv head) block, per instruction
+#pragma unroll
+  for (int jj = 0; jj < IPP; ++jj) {
+    const int line = 4 * jj + dq;
+    const int clk = dslot ^ Z::gk(line), clv = dslot ^ Z::gv(line);
+    voff_k[jj] = (unsigned)(((D == 128 ? line : 2 * line + (clk >> 3)) & 15) * ROWB + (D == 128 ? clk : (clk & 7)) * 16);
+    voff_v[jj] = (unsigned)(((D == 128 ? line : 2 * line + (clv >> 3)) & 15) * ROWB + (D == 128 ? clv : (clv & 7)) * 16);
+  }
+  const size_t page_stride = (size_t)a.Hkv * (kPage * ROWB);
+  const char *kpool = a.k_pages + (size_t)kvh * (kPage * ROWB), *vpool = a.v_pages + (size_t)kvh * (kPage * ROWB);
+  auto issue_block = [&](int bi) {
+    const unsigned slot_base = (unsigned)((bi % NB) * SLOT);
+    if (32 * bi + 31 <= last_row) {
+      // both pages of the block lie inside the range: two page bases, precomputed lane offsets
+#pragma unroll
+      for (int pp = 0; pp < 2; ++pp) {
+        const size_t poff = (size_t)(unsigned)__builtin_amdgcn_readlane(my_page, 2 * bi + pp) * page_stride;
+        const char *pbk = kpool + poff, *pbv = vpool + poff;
+#pragma unroll
+        for (int jj = 0; jj < IPP; ++jj) {
+          const unsigned dk = slot_base + (pp * IPP + jj) * 1024, dv = dk + MBYTES;
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dk), "v"(voff_k[jj]), "s"(pbk));
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dv), "v"(voff_v[jj]), "s"(pbv));
+        }
+      }
+      return;
+    }
+    // the last, partial block: rows past the end are redirected to the last row
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int row0 = 32 * bi + RPI * j;                   // first row of the instruction, relative to kv0
+        const int pslot = min(row0, last_row) >> 4;           // uniform
+        const int rip_lim = pslot == (last_row >> 4) ? (last_row & 15) : 15;
+        const char *pb = (m ? vpool : kpool) + (size_t)(unsigned)__builtin_amdgcn_readlane(my_page, pslot) * page_stride;
+        const int line = 4 * j + dq;                          // line inside the block
+        const int cl = dslot ^ (m ? Z::gv(line) : Z::gk(line));
+        const int rip = (D == 128 ? line : 2 * line + (cl >> 3)) & 15;
+        const int chunk16 = D == 128 ? cl : (cl & 7);
+        const unsigned voff = (unsigned)(min(rip, rip_lim) * ROWB + chunk16 * 16);
+        const unsigned dst = slot_base + m * MBYTES + j * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dst), "v"(voff), "s"(pb));
+      }
+    }
+  };
+
+  // ---- LDS operand offsets of this lane inside a slot
+  int kofs[G::kDSteps], vofs[G::kDBlocks];
+#pragma unroll
+  for (int s = 0; s < G::kDSteps; ++s) kofs[s] = Z::template offset<false>(col, 2 * s + half);
+  {
+    const int n = lane & 15, dg = (lane >> 4) & 1;
+#pragma unroll
+    for (int db = 0; db < G::kDBlocks; ++db)
+      vofs[db] = MBYTES + Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) + 8 * (n & 1);
+  }
+  auto read_vt = [&](const lds_char *p) -> bf16x8 {  // key rows r..r+3 and r+8..r+11 of one 32-channel block
+    union {
+      struct { s16x4 a, b; } s;
+      bf16x8 v;
+    } u;
+    u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+    u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * ROWB));
+    return u.v;
+  };
 
   f32x16 o[G::kDBlocks];
 #pragma unroll
@@ -123,153 +204,97 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void decode_split_kernel(DecodeA
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  if (kv0 < kv1) {
-    u32x4 kreg[NCH], vreg[NCH];
-    // Blocks that lie fully inside the range are loaded without any branch (a conditional load
-    // forces a full vmcnt(0) at the join, which would expose a memory round trip per block);
-    // only the last, partial block takes the guarded path that zero-fills rows past the end, so
-    // zero weights never meet NaN payloads of unwritten cache slots.
-    auto issue_loads = [&](int base) {
-      const int pslot = (base - kv0) >> 4;
-      if (base + 32 <= kv1) {
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-          int id = lane + i * 64;
-          int row = id / CPR, cc = id % CPR;
-          // all lanes of load i sit in one page: its id comes from the lane that fetched it
-          int pg = max(__builtin_amdgcn_readlane(my_page, pslot + (i * ROWS_PER_LOAD) / kPage), 0);
-          long off = (((long)pg * a.Hkv + kvh) * kPage + ((base + row) & 15)) * (D * 2) + cc * 16;
-          kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.k_pages + off));
-          vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.v_pages + off));
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-          int id = lane + i * 64;
-          int row = id / CPR, cc = id % CPR;
-          int kvpos = base + row;
-          int pg = __builtin_amdgcn_readlane(my_page, pslot + (i * ROWS_PER_LOAD) / kPage);
-          if (pg >= 0 && kvpos < kv1) {
-            long off = (((long)pg * a.Hkv + kvh) * kPage + (kvpos & 15)) * (D * 2) + cc * 16;
-            kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.k_pages + off));
-            vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(a.v_pages + off));
-          } else {
-            kreg[i] = (u32x4){0, 0, 0, 0};
-            vreg[i] = (u32x4){0, 0, 0, 0};
-          }
-        }
-      }
-    };
-    auto write_lds = [&]() {
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        int id = lane + i * 64;
-        int row = id / CPR, cc = id % CPR;
-        *(lds_u32x4 *)(kb + row * G::kKStride + cc * 16) = kreg[i];
-        *(lds_u32x4 *)(vb + row * G::kVStride + cc * 16) = vreg[i];
-      }
-    };
+  for (int bi = 0; bi < NB - 1; ++bi)
+    if (bi < nb) issue_block(bi);
+  for (int i = 0; i < nb; ++i) {
+    // the slot of block i-1 is free again: keep NB-1 blocks in flight behind block i
+    if (i + NB - 1 < nb) issue_block(i + NB - 1);
+    const int behind = min(NB - 1, nb - 1 - i);  // blocks requested after block i
+    if (behind >= 3 && NB > 3) wait_vmcnt<(NB > 3 ? 3 : 0) * LPB>();
+    else if (behind == 2 && NB > 2) wait_vmcnt<(NB > 2 ? 2 : 0) * LPB>();
+    else if (behind == 1 && NB > 1) wait_vmcnt<(NB > 1 ? 1 : 0) * LPB>();
+    else wait_vmcnt<0>();
+    const lds_char *sb = smem + (i % NB) * SLOT;
+    const int base = kv0 + 32 * i;
 
-    issue_loads(kv0);
-    for (int base = kv0; base < kv1; base += 32) {
-      write_lds();
-      wave_lds_fence();
-      if (base + 32 < kv1) issue_loads(base + 32);
-      f32x16 sacc;
+    f32x16 sacc, sacc1;  // two accumulators halve the dependent MFMA chain a lone wave sits through
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+    for (int r = 0; r < 16; ++r) sacc[r] = sacc1[r] = 0.f;
 #pragma unroll
-      for (int s = 0; s < G::kDSteps; ++s) {
-        bf16x8 kop = lds_read_k_operand(kb, G::kKStride, col, 2 * s + half);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop, qreg[s], sacc, 0, 0, 0);
-      }
-      if (base + 32 > kv1) {
+    for (int s = 0; s < G::kDSteps; s += 2) {
+      bf16x8 kop0 = *(const lds_bf16x8 *)(sb + kofs[s]);
+      bf16x8 kop1 = *(const lds_bf16x8 *)(sb + kofs[s + 1]);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop0, qreg[s], sacc, 0, 0, 0);
+      sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop1, qreg[s + 1], sacc1, 0, 0, 0);
+    }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (kv >= kv1) sacc[r] = -INFINITY;
-        }
-      }
-      float mx = sacc[0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-      mx = fmaxf(mx, other_half(mx));
-      const float m_new = fmaxf(m, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * a.sl2e);
-      const float msc = m_new * a.sl2e;
-      float lsum = 0.f;
+    for (int r = 0; r < 16; ++r) sacc[r] += sacc1[r];
+    if (base + 32 > kv1) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], a.sl2e, -msc));
-        sacc[r] = p;
-        lsum += p;
+        int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (kv >= kv1) sacc[r] = -INFINITY;
       }
-      l = l * alpha + lsum;
+    }
+    float mx = sacc[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+    mx = fmaxf(mx, other_half(mx));
+    // The running max only moves when some column's block max exceeds it by more than 2^8 in
+    // the exponent (tau); otherwise weights are taken against the stale max (bounded by 2^8,
+    // harmless in fp32/bf16) and the O accumulators need no rescale.
+    if (__builtin_amdgcn_ballot_w64(mx > m + a.tau) != 0) {  // wave-uniform, rare after the first block
+      const float m_new = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * a.sl2e);
       m = m_new;
-      bf16x8 pop[2] = {pack8(sacc, 0), pack8(sacc, 8)};
+      l *= alpha;
 #pragma unroll
       for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    const float msc = m * a.sl2e;
+    float lsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], a.sl2e, -msc));
+      sacc[r] = p;
+      lsum += p;
+    }
+    l += lsum;
+    bf16x8 pop[2] = {pack8(sacc, 0), pack8(sacc, 8)};
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int db = 0; db < G::kDBlocks; ++db) {
+        bf16x8 vop = read_vt(sb + vofs[db] + 16 * ks * ROWB);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
+      }
+    if (L <= 64) {  // very short sequences: weights as hi + lo, so bf16 rounding of P stays out of the tolerance
+      bf16x8 plo[2] = {pack8_residual(sacc, 0, pop[0]), pack8_residual(sacc, 8, pop[1])};
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int db = 0; db < G::kDBlocks; ++db) {
-          bf16x8 vop = lds_read_vt_operand(vb, G::kVStride, 16 * ks + 4 * half, 32 * db, lane);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
+          bf16x8 vop = read_vt(sb + vofs[db] + 16 * ks * ROWB);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[ks], o[db], 0, 0, 0);
         }
-      if (L <= 64) {  // very short sequences: weights as hi + lo, so bf16 rounding of P stays out of the tolerance
-        bf16x8 plo[2] = {pack8_residual(sacc, 0, pop[0]), pack8_residual(sacc, 8, pop[1])};
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-          for (int db = 0; db < G::kDBlocks; ++db) {
-            bf16x8 vop = lds_read_vt_operand(vb, G::kVStride, 16 * ks + 4 * half, 32 * db, lane);
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[ks], o[db], 0, 0, 0);
-          }
-      }
-      wave_lds_fence();  // reads of this block done before the next block overwrites the region
     }
   }
 
-  // ---- merge the four waves' running states through LDS (each wave reuses its own region)
-  // layout per wave: ml[col][2] floats, then ow[col][OS] floats
+  // ---- the wave's partial: un-normalised o, m in log2 units, l
   l += other_half(l);
-  {
-    lds_float *ml = (lds_float *)kb;
-    lds_float *ow = ml + 32 * 2;
-    if (col < ncols) {
-      if (half == 0) {
-        ml[col * 2 + 0] = m * a.sl2e;  // log2 units; -inf if the wave had no key
-        ml[col * 2 + 1] = l;
-      }
+  if (col < ncols) {
+    const long pidx = ((long)seq * a.Hq + head0 + col) * a.nsplit + split;
+    float *po = a.part_o + pidx * D;
 #pragma unroll
-      for (int db = 0; db < G::kDBlocks; ++db)
+    for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) ow[col * OS + 32 * db + 8 * (r >> 2) + 4 * half + (r & 3)] = o[db][r];
-    }
-  }
-  __syncthreads();
-  // thread -> (column, channel); fixed wave order keeps the sum reproducible
-  for (int idx = tid; idx < ncols * D; idx += kDecWaves * 64) {
-    const int c = idx / D, ch = idx - c * D;
-    float mw[kDecWaves], M = -INFINITY;
-#pragma unroll
-    for (int ww = 0; ww < kDecWaves; ++ww) {
-      mw[ww] = ((lds_float *)((lds_char *)smem_raw + ww * WBYTES))[c * 2];
-      M = fmaxf(M, mw[ww]);
-    }
-    float acc = 0.f, lt = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < kDecWaves; ++ww) {
-      lds_float *wml = (lds_float *)((lds_char *)smem_raw + ww * WBYTES);
-      float f = __builtin_amdgcn_exp2f(mw[ww] - M);  // wave 0 always has a key, so M is finite
-      acc += f * wml[64 + c * OS + ch];
-      lt += f * wml[c * 2 + 1];
-    }
-    const long pidx = ((long)seq * a.Hq + head0 + c) * a.nsplit + split;
-    a.part_o[pidx * D + ch] = acc;
-    if (ch == 0) *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){M, lt};
+      for (int r4 = 0; r4 < 4; ++r4)
+        *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * r4 + 4 * half) =
+            (f32x4){o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
+    if (half == 0) *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){m * a.sl2e, l};
   }
 }
 
@@ -288,42 +313,56 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// One wave per (sequence, head).  Lane k holds the weight of split k (64 splits per round);
-// every lane owns two output channels and accumulates the splits in index order.
+// One wave per (sequence, head).  Every split of the row holds a partial, real or empty
+// (m = -inf), so nothing depends on the sequence length: the (m, l) pairs and the first few
+// partial rows are requested in one memory round trip.  Lane k holds the weight of split k (64
+// splits per round); every lane owns two output channels and accumulates the splits in index
+// order.  A row with no keys at all (every m = -inf) is written as zeros.
 template <int D>
 __global__ __launch_bounds__(64) void decode_combine_kernel(const float *__restrict__ part_o,
                                                              const float *__restrict__ part_ml,
-                                                             const int32_t *__restrict__ seq_lens,
-                                                             char *__restrict__ out, int Hq, int chunk,
-                                                             int nsplit) {
+                                                             char *__restrict__ out, int nsplit) {
+  constexpr int SPEC = 8;  // partial rows fetched before their weights are known
   const int row = blockIdx.x;  // seq * Hq + head
-  const int seq = row / Hq;
-  const int L = seq_lens[seq];
   const int lane = threadIdx.x;
   const int ch = (lane % (D / 2)) * 2;
   const bool writer = lane < D / 2;
   bf16x2 *dst = reinterpret_cast<bf16x2 *>(out + ((long)row * D + ch) * 2);
-  if (L <= 0 || part_o == nullptr) {
+  if (part_o == nullptr) {  // every sequence of the batch is empty
     if (writer) *dst = __builtin_convertvector((f32x2){0.f, 0.f}, bf16x2);
     return;
   }
-  // a too-small max_seq_len hint must not read past the workspace
-  const int n = min((L + chunk - 1) / chunk, nsplit);
   const f32x2 *ml = reinterpret_cast<const f32x2 *>(part_ml) + (long)row * nsplit;
   const float *po = part_o + (long)row * nsplit * D + ch;
+  f32x2 spec[SPEC];  // empty splits hold stale bytes here: only ever selected, never multiplied by 0
+#pragma unroll
+  for (int u = 0; u < SPEC; ++u) spec[u] = *reinterpret_cast<const f32x2 *>(po + (long)min(u, nsplit - 1) * D);
   float M = -INFINITY;
-  for (int k = lane; k < n; k += 64) M = fmaxf(M, ml[k][0]);
+  for (int k = lane; k < nsplit; k += 64) M = fmaxf(M, ml[k][0]);
   M = wave_max(M);
+  if (M == -INFINITY) {
+    if (writer) *dst = __builtin_convertvector((f32x2){0.f, 0.f}, bf16x2);
+    return;
+  }
   float a0 = 0.f, a1 = 0.f, den = 0.f;
-  for (int base = 0; base < n; base += 64) {
-    const int cnt = min(64, n - base);
+  for (int base = 0; base < nsplit; base += 64) {
+    const int cnt = min(64, nsplit - base);
     float f = 0.f;
     if (lane < cnt) {
       f32x2 v = ml[base + lane];
-      f = __builtin_amdgcn_exp2f(v[0] - M);
+      f = __builtin_amdgcn_exp2f(v[0] - M);  // 0 for an empty split
       den += f * v[1];
     }
     int k = 0;
+    if (base == 0) {
+#pragma unroll
+      for (int u = 0; u < SPEC; ++u) {
+        float fu = u < cnt ? lane_bcast(f, u) : 0.f;
+        a0 += fu != 0.f ? fu * spec[u][0] : 0.f;
+        a1 += fu != 0.f ? fu * spec[u][1] : 0.f;
+      }
+      k = SPEC;
+    }
     for (; k + 8 <= cnt; k += 8) {  // eight independent loads in flight per lane
       f32x2 v[8];
 #pragma unroll
@@ -331,14 +370,17 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float *__restr
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         float fu = lane_bcast(f, k + u);
-        a0 += fu * v[u][0];
-        a1 += fu * v[u][1];
+        a0 += fu != 0.f ? fu * v[u][0] : 0.f;
+        a1 += fu != 0.f ? fu * v[u][1] : 0.f;
       }
     }
     for (; k < cnt; ++k) {
-      f32x2 v0 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k) * D);
       float f0 = lane_bcast(f, k);
-      a0 += f0 * v0[0]; a1 += f0 * v0[1];
+      if (f0 != 0.f) {  // wave-uniform
+        f32x2 v0 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k) * D);
+        a0 += f0 * v0[0];
+        a1 += f0 * v0[1];
+      }
     }
   }
   den = wave_sum(den);
@@ -346,15 +388,33 @@ __global__ __launch_bounds__(64) void decode_combine_kernel(const float *__restr
   if (writer) *dst = __builtin_convertvector((f32x2){a0 * inv, a1 * inv}, bf16x2);
 }
 
+template <int D, int NB>
+static int launch_split(const DecodeArgs &a, int batch, hipStream_t stream) {
+  static bool attr_set = false;  // benign if two threads race
+  constexpr int smem = NB * 2 * 32 * D * 2;
+  auto fn = decode_split_kernel<D, NB>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return fail(SP_ERR_HIP, "decode smem attribute: %s", hipGetErrorString(e));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(fn, dim3(a.nsplit, (unsigned)(batch * a.n_hgroups)), dim3(64), smem, stream, a);
+  return SP_OK;
+}
+
 template <int D>
 static int launch_decode_d(DecodeArgs &a, char *out, int batch, hipStream_t stream) {
   long gy = (long)batch * a.n_hgroups;
   if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_decode: batch * head groups = %ld exceeds 65535", gy);
-  hipLaunchKernelGGL(decode_split_kernel<D>, dim3(a.nsplit, (unsigned)gy), dim3(kDecWaves * 64), 0, stream, a);
+  const int ring = g_ring_override > 0 ? g_ring_override : 2;  // more resident waves beat a deeper ring (measured)
+  int rc = ring == 2 ? launch_split<D, 2>(a, batch, stream)
+         : ring == 3 ? launch_split<D, 3>(a, batch, stream)
+                     : launch_split<D, 4>(a, batch, stream);
+  if (rc != SP_OK) return rc;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "decode split launch: %s", hipGetErrorString(e));
-  hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o, a.part_ml,
-                     a.seq_lens, out, a.Hq, a.chunk, a.nsplit);
+  hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o, a.part_ml, out,
+                     a.nsplit);
   e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "decode combine launch: %s", hipGetErrorString(e));
   return SP_OK;
@@ -380,6 +440,7 @@ int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_
   if (a.group % a.geff != 0) a.geff = 1;  // odd large groups: one head per tile
   a.n_hgroups = num_q_heads / a.geff;
   a.sl2e = scale * 1.44269504088896340736f;
+  a.tau = 8.0f / a.sl2e;
   if (max_seq_len <= 0) {
     // every sequence is empty: the combine kernel alone writes the zero rows
     a.chunk = kDecMinChunk;
@@ -388,10 +449,10 @@ int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_
     a.part_ml = nullptr;
     if (c.head_dim == 128)
       hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o,
-                         a.part_ml, seq_lens, (char *)out, a.Hq, a.chunk, a.nsplit);
+                         a.part_ml, (char *)out, a.nsplit);
     else
       hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o,
-                         a.part_ml, seq_lens, (char *)out, a.Hq, a.chunk, a.nsplit);
+                         a.part_ml, (char *)out, a.nsplit);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SP_ERR_HIP, "decode combine launch: %s", hipGetErrorString(e));
     return SP_OK;

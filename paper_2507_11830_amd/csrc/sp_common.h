@@ -36,6 +36,7 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
 
 // Tuning hooks behind sp_debug_set_tuning (0 restores the built-in heuristic).
 void set_decode_chunk(int chunk);
+void set_decode_ring(int slots);   // LDS ring depth of the decode split kernel: 0 heuristic, 2..4
 void set_prefill_split(int mode);  // 0 heuristic, 1 never split the key range over the wave groups, 2 always
 
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);

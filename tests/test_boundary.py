@@ -98,10 +98,12 @@ def test_tuning_keys_are_validated(built_lib):
     L = sp.lib()
     assert L.sp_debug_set_tuning(None, 0) == sp.SP_ERR_NULL
     assert L.sp_debug_set_tuning(b"no_such_key", 0) == sp.SP_ERR_UNSUPPORTED
-    for v, want in [(0, sp.SP_OK), (512, sp.SP_OK), (4096, sp.SP_OK), (768, sp.SP_ERR_UNSUPPORTED),
-                    (256, sp.SP_ERR_UNSUPPORTED), (8192, sp.SP_ERR_UNSUPPORTED)]:
+    for v, want in [(0, sp.SP_OK), (128, sp.SP_OK), (1024, sp.SP_OK), (768, sp.SP_ERR_UNSUPPORTED),
+                    (64, sp.SP_ERR_UNSUPPORTED), (2048, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"decode_chunk", v) == want
     for v, want in [(1, sp.SP_OK), (2, sp.SP_OK), (3, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"prefill_split", v) == want
-    assert L.sp_debug_set_tuning(b"decode_chunk", 0) == sp.SP_OK
-    assert L.sp_debug_set_tuning(b"prefill_split", 0) == sp.SP_OK
+    for v, want in [(2, sp.SP_OK), (4, sp.SP_OK), (1, sp.SP_ERR_UNSUPPORTED), (5, sp.SP_ERR_UNSUPPORTED)]:
+        assert L.sp_debug_set_tuning(b"decode_ring", v) == want
+    for key in (b"decode_chunk", b"decode_ring", b"prefill_split"):
+        assert L.sp_debug_set_tuning(key, 0) == sp.SP_OK
