@@ -226,12 +226,110 @@ def extra_big_decode(sp, iters=10):
             "kv_bytes": nbytes}
 
 
+def extra_chunked_prefill(sp):
+    """C4: 32 sequences with lognormal lengths, second half of each prefilled in chunks of <= 512
+    tokens against the cached prefix; every step = append + prefill, both timed."""
+    import torch
+    import workloads as W
+
+    w = W.c4_chunked()
+    cache = sp.KVCache.empty(w.num_pages, w.Hkv, w.d)
+    bt = _dev_i32(w.block_table)
+    steps, flops, t_att, t_app = 0, 0, 0.0, 0.0
+    per_step = []
+    for st in w.steps():
+        k, v = _dev_bf16(st.k_new), _dev_bf16(st.v_new)
+        cu, ctx = _dev_i32(st.cu_new), _dev_i32(st.ctx_lens)
+        if st.kind == "fill":
+            sp.sp_kv_append(cache, k, v, cu, ctx, bt)
+            continue
+        q = _dev_bf16(st.q)
+        out = torch.empty_like(q)
+        mq, mkv = int(st.new_lens.max()), int(st.seq_lens.max())
+        need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], w.Hq, w.d)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+        app = lambda: sp.sp_kv_append(cache, k, v, cu, ctx, bt)      # idempotent: same rows, same slots
+        att = lambda: sp.sp_attn_prefill(cache, q, out, cu, ctx, bt, mq, mkv, float(w.scale), workspace=ws)
+        _, per = time_phases([app, att], 5, 1)
+        f = W.prefill_flops(st, w.Hq, w.d)
+        per_step.append({"tokens": int(st.new_lens.sum()), "ms": per[1], "TFLOPs": f / per[1] / 1e9})
+        steps += 1
+        flops += f
+        t_app += per[0]
+        t_att += per[1]
+    return {"workload": f"C4 mixed chunked prefill, 32 sequences, {steps} steps of <=512-token chunks on cached "
+                        "prefixes, 8q/1kv, d=128", "ms": t_att, "ms_kv_append": t_app, "TFLOPs": flops / t_att / 1e9,
+            "frac_of_bf16_peak": flops / t_att / 1e9 / PEAK_BF16_TFLOPS, "per_step": per_step}
+
+
+def extra_shift_decode(sp, steps=64):
+    """C5b: right after a 32768-token prefill, decode steps on the SAME cache and block table
+    (append one token, then attend over 32769+t keys).  The 16.8 MB of K/V stay in the
+    last-level cache, so this is a launch- and latency-bound figure, not an HBM one."""
+    import torch
+    import workloads as W
+
+    w = W.c5_long(decode_steps=0)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    T = 32768
+    cache = sp.KVCache.empty(w.num_pages, 1, 128)
+    bt = _dev_i32(w.block_table)
+    k = torch.randn((T + steps, 1, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn((T + steps, 1, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((steps, 8, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty((1, 8, 128), device="cuda", dtype=torch.bfloat16)
+    sp.sp_kv_append(cache, k[:T], v[:T], _dev_i32([0, T]), _dev_i32([0]), bt)
+    ws = torch.empty(sp.sp_attn_decode_workspace_size(1, T + steps, 8, 128), dtype=torch.uint8, device="cuda")
+    cu1 = _dev_i32([0, 1])
+    ctxs = [_dev_i32([T + t]) for t in range(steps)]
+    lens = [_dev_i32([T + t + 1]) for t in range(steps)]
+    state = {"t": 0}
+
+    def app():
+        t = state["t"]
+        sp.sp_kv_append(cache, k[T + t:T + t + 1], v[T + t:T + t + 1], cu1, ctxs[t], bt)
+
+    def att():
+        t = state["t"]
+        sp.sp_attn_decode(cache, q[t:t + 1], out, lens[t], bt, T + steps, float(w.scale), ws)
+        state["t"] = (t + 1) % steps
+
+    _, per = time_phases([app, att], steps, 4)
+    nbytes = W.decode_bytes(np.array([T + steps // 2]), 8, 1, 128)
+    return {"workload": f"C5b decode steps on the cache the 32768-token prefill filled (same block table, no re-layout), "
+                        f"{steps} steps", "us_per_step_attn": per[1] * 1e3, "us_per_step_kv_append": per[0] * 1e3,
+            "GBps_cache_resident": nbytes / per[1] / 1e6}
+
+
+def ceilings(sp):
+    """What this machine delivers for the two bounding resources: a register-resident bf16 MFMA loop
+    and a 16 B/lane streaming read of 2 GiB (both kernels live in the library)."""
+    import torch
+
+    sink = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    iters = 20000
+    fl = {}
+
+    def mf():
+        fl["f"] = sp.sp_debug_ceiling_mfma(iters, sink)
+
+    _, per = time_phases([mf], 5, 2)
+    clk = sink[:16].view(torch.int64).cpu().numpy()
+    mhz = float(clk[0]) / (float(clk[1]) / 100e6) / 1e6 if clk[1] > 0 else None
+    buf = torch.empty(1 << 31, dtype=torch.uint8, device="cuda")
+    buf.fill_(1)
+    _, per2 = time_phases([lambda: sp.sp_debug_ceiling_stream(buf, sink)], 5, 2)
+    return {"mfma_loop_TFLOPs": fl["f"] / per[0] / 1e9, "mfma_loop_shader_clock_MHz": mhz,
+            "stream_read_GBps": float(buf.numel()) / per2[0] / 1e6}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--no-extras", action="store_true", help="skip the C5a / C5c side measurements")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the ceiling kernels and the C5a / C5c / C4 / C5b side measurements")
     ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5c", "copy"],
                     help="main = the step described above; c5a / c5c = only that side workload "
                          "(used for per-kernel profiles); copy = a plain 1 GiB device copy, the "
@@ -308,7 +406,17 @@ def main():
                             "kernel": "decode_split_kernel + decode_combine_kernel"},
     }
     if not args.no_extras:
-        res["other_workloads"] = [extra_long_prefill(sp), extra_big_decode(sp)]
+        ceil = ceilings(sp)
+        res["ceilings"] = ceil
+        res["roofline"]["frac_of_measured_mfma_loop"] = tflops / ceil["mfma_loop_TFLOPs"]
+        res["roofline_decode"]["frac_of_measured_stream_read"] = gbps / ceil["stream_read_GBps"]
+        res["other_workloads"] = [extra_long_prefill(sp), extra_big_decode(sp), extra_chunked_prefill(sp),
+                                  extra_shift_decode(sp)]
+        for o in res["other_workloads"]:
+            if "TFLOPs" in o:
+                o["frac_of_measured_mfma_loop"] = o["TFLOPs"] / ceil["mfma_loop_TFLOPs"]
+            if "GBps" in o:
+                o["frac_of_measured_stream_read"] = o["GBps"] / ceil["stream_read_GBps"]
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wp, pre.st)
     print(json.dumps(res))

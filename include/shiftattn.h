@@ -88,7 +88,12 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  *                   nothing; it only bounds loops)
  *   scale           softmax scale, normally 1/sqrt(head_dim)
  *   causal          must be 1
- *   workspace       unused by the current kernels; may be NULL with workspace_bytes 0
+ *   workspace       optional device scratch (contents need no initialisation).  With at least
+ *                   sp_attn_prefill_workspace_size(...) bytes the library may cut long key
+ *                   ranges into pieces computed by separate workgroups and merged by a
+ *                   log-sum-exp combine pass, which it does for batches of few query tokens on
+ *                   long cached prefixes; with NULL / 0 (or less than that) it uses fewer
+ *                   pieces or none.  The result is the same up to fp32 summation order.
  * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax.
  */
 int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
@@ -113,7 +118,8 @@ int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out,
                    int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads,
                    float scale, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Bytes of workspace the two attention calls need for the given host-side shape. */
+/* Bytes of workspace for the given host-side shape: what sp_attn_decode requires, and what lets
+ * sp_attn_prefill split key ranges (0 when the batch has too many query rows for that to pay). */
 size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens,
                                       int32_t num_q_heads, int32_t head_dim);
 size_t sp_attn_decode_workspace_size(int32_t batch, int32_t max_seq_len, int32_t num_q_heads,
@@ -135,6 +141,9 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  *                   [128, 1024].  Changes what sp_attn_decode_workspace_size returns.
  *   "decode_ring"   32-key blocks a decode wave keeps in its LDS ring (one computed on, the
  *                   rest in flight): 0 (built-in choice) or 2..4.
+ *   "prefill_kv_splits" pieces the key range of a prefill query tile is cut into when a
+ *                   workspace is given: 0 (built-in heuristic) or 1..16 (still bounded by the
+ *                   workspace size).
  *   "prefill_split" how a prefill workgroup's two wave groups divide the work: 0 (built-in
  *                   heuristic on the grid size), 1 (neighbouring query columns, shared key
  *                   tiles), 2 (same query columns, alternate key tiles, merged at the end).
@@ -142,6 +151,25 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  * Returns SP_OK, SP_ERR_NULL or SP_ERR_UNSUPPORTED (unknown key / value out of range).
  */
 int sp_debug_set_tuning(const char *key, int32_t value);
+
+/*
+ * sp_debug_ceiling_mfma / sp_debug_ceiling_stream — measurement aids, not part of the hot path:
+ * the two reference kernels a benchmark times to see what THIS chip delivers for the resources
+ * the attention kernels are bound by (the published peaks assume the full boost clock).
+ *   mfma    a register-resident bf16 32x32x16 MFMA loop on every CU: 8 waves per CU, `iters`
+ *           rounds of four MFMAs each.  *host_flops (host pointer) receives the number of flops
+ *           the launch performs.  `sink` is device scratch of at least 16 + 4 * CUs bytes;
+ *           after the launch its first two uint64 hold the shader-clock cycles and the ticks of
+ *           the constant 100 MHz counter that workgroup 0 spent in the loop (their ratio is the
+ *           clock the chip sustained under that load).
+ *   stream  reads `bytes` (a multiple of 16) from device buffer `buf` once, 16 bytes per lane,
+ *           nontemporal; `sink` is device scratch of at least 32 * CUs bytes.
+ * Both only enqueue on `stream`; the caller times them.
+ */
+int sp_debug_ceiling_mfma(int32_t iters, double *host_flops, void *sink, size_t sink_bytes,
+                          void *stream);
+int sp_debug_ceiling_stream(const void *buf, size_t bytes, void *sink, size_t sink_bytes,
+                            void *stream);
 
 const char *sp_status_string(int status); /* static string                              */
 const char *sp_last_error(void);          /* thread-local detail of the last failure    */

@@ -25,7 +25,7 @@ SP_ERR_HIP = -5
 EXPORTS = (
     "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_attn_prefill_workspace_size",
     "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_set_tuning",
-    "sp_status_string",
+    "sp_debug_ceiling_mfma", "sp_debug_ceiling_stream", "sp_status_string",
     "sp_last_error", "sp_version",
 )
 
@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.sp_debug_validate_metadata.restype = ctypes.c_int
         L.sp_debug_set_tuning.argtypes = [ctypes.c_char_p, i32]
         L.sp_debug_set_tuning.restype = ctypes.c_int
+        L.sp_debug_ceiling_mfma.argtypes = [i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
+        L.sp_debug_ceiling_mfma.restype = ctypes.c_int
+        L.sp_debug_ceiling_stream.argtypes = [vp, sz, vp, sz, vp]
+        L.sp_debug_ceiling_stream.restype = ctypes.c_int
         L.sp_status_string.argtypes = [ctypes.c_int]
         L.sp_status_string.restype = ctypes.c_char_p
         L.sp_last_error.restype = ctypes.c_char_p
@@ -185,3 +189,19 @@ def sp_debug_validate_metadata(cache: KVCache, seq_lens, block_table) -> None:
 
 def sp_debug_set_tuning(key: str, value: int) -> None:
     _check(lib().sp_debug_set_tuning(key.encode(), int(value)))
+
+
+def sp_debug_ceiling_mfma(iters: int, sink, stream=None) -> float:
+    """Enqueues the MFMA-only reference loop; returns the flops it performs.  `sink`: cuda uint8 tensor."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().sp_debug_ceiling_mfma(int(iters), ctypes.byref(flops), _ptr(sink),
+                                       sink.numel() * sink.element_size(), _stream(stream)))
+    return flops.value
+
+
+def sp_debug_ceiling_stream(buf, sink, stream=None) -> int:
+    """Enqueues the streaming-read reference kernel over all of `buf`; returns the bytes it reads."""
+    nbytes = buf.numel() * buf.element_size()
+    _check(lib().sp_debug_ceiling_stream(_ptr(buf), nbytes, _ptr(sink), sink.numel() * sink.element_size(),
+                                         _stream(stream)))
+    return nbytes

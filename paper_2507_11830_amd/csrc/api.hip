@@ -73,8 +73,6 @@ int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
                     int32_t total_q_tokens, int32_t max_q_len, int32_t max_kv_len,
                     int32_t num_q_heads, float scale, int32_t causal, void *workspace,
                     size_t workspace_bytes, void *stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   if (int rc = check_cache(cache)) return rc;
   if (int rc = check_heads(cache, num_q_heads)) return rc;
   if (causal != 1) return fail(SP_ERR_UNSUPPORTED, "causal=%d (only causal attention)", causal);
@@ -87,7 +85,7 @@ int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
   if (max_pages_per_seq == 0) return fail(SP_ERR_BAD_SHAPE, "max_pages_per_seq=0 with queries");
   return launch_prefill(*cache, q, out, cu_seqlens_q, ctx_lens, block_table, batch, max_pages_per_seq,
                         total_q_tokens, max_q_len, max_kv_len, num_q_heads, scale,
-                        (hipStream_t)stream);
+                        workspace_bytes ? workspace : nullptr, workspace_bytes, (hipStream_t)stream);
 }
 
 int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out, const int32_t *seq_lens,
@@ -111,7 +109,12 @@ int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out, const i
                        num_q_heads, scale, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
-size_t sp_attn_prefill_workspace_size(int32_t, int32_t, int32_t, int32_t) { return 0; }
+size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens, int32_t num_q_heads,
+                                      int32_t head_dim) {
+  (void)batch;
+  if (total_q_tokens <= 0 || num_q_heads <= 0 || head_dim <= 0) return 0;
+  return prefill_workspace_bytes(total_q_tokens, num_q_heads, head_dim);
+}
 
 size_t sp_attn_decode_workspace_size(int32_t batch, int32_t max_seq_len, int32_t num_q_heads,
                                      int32_t head_dim) {
@@ -158,6 +161,11 @@ int sp_debug_set_tuning(const char *key, int32_t value) {
     if (value != 0 && (value < 2 || value > 4))
       return fail(SP_ERR_UNSUPPORTED, "decode_ring=%d (0, or 2..4)", value);
     set_decode_ring(value);
+    return SP_OK;
+  }
+  if (!strcmp(key, "prefill_kv_splits")) {
+    if (value < 0 || value > 16) return fail(SP_ERR_UNSUPPORTED, "prefill_kv_splits=%d (0..16)", value);
+    set_prefill_kv_splits(value);
     return SP_OK;
   }
   if (!strcmp(key, "prefill_split")) {

@@ -313,79 +313,131 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// One wave per (sequence, head).  Every split of the row holds a partial, real or empty
-// (m = -inf), so nothing depends on the sequence length: the (m, l) pairs and the first few
-// partial rows are requested in one memory round trip.  Lane k holds the weight of split k (64
-// splits per round); every lane owns two output channels and accumulates the splits in index
-// order.  A row with no keys at all (every m = -inf) is written as zeros.
-template <int D>
-__global__ __launch_bounds__(64) void decode_combine_kernel(const float *__restrict__ part_o,
-                                                             const float *__restrict__ part_ml,
-                                                             char *__restrict__ out, int nsplit) {
+// One workgroup of W waves per output row (a (sequence, head) of a decode batch, or a
+// (token, head) of a key-split prefill).  Every split of the row holds a partial, real or
+// empty (m = -inf), so nothing depends on sequence lengths: the (m, l) pairs and the first few
+// partial rows are requested in one memory round trip.  Wave w reduces the contiguous range of
+// splits [w * per, (w + 1) * per): lane k holds the weight of the range's k-th split (64 per
+// round), every lane owns two output channels and accumulates splits in index order; the W
+// running states are then merged in wave order, so the result does not depend on timing.
+// A row with no keys at all (every m = -inf) is written as zeros.
+template <int D, int W>
+__global__ __launch_bounds__(64 * W) void combine_kernel(const float *__restrict__ part_o,
+                                                         const float *__restrict__ part_ml,
+                                                         char *__restrict__ out, int nsplit) {
   constexpr int SPEC = 8;  // partial rows fetched before their weights are known
-  const int row = blockIdx.x;  // seq * Hq + head
-  const int lane = threadIdx.x;
+  const int row = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ch = (lane % (D / 2)) * 2;
-  const bool writer = lane < D / 2;
+  const bool writer = threadIdx.x < D / 2;
   bf16x2 *dst = reinterpret_cast<bf16x2 *>(out + ((long)row * D + ch) * 2);
   if (part_o == nullptr) {  // every sequence of the batch is empty
     if (writer) *dst = __builtin_convertvector((f32x2){0.f, 0.f}, bf16x2);
     return;
   }
+  const int per = (nsplit + W - 1) / W;
+  const int k0 = min(w * per, nsplit), k1 = min(nsplit, k0 + per);
   const f32x2 *ml = reinterpret_cast<const f32x2 *>(part_ml) + (long)row * nsplit;
   const float *po = part_o + (long)row * nsplit * D + ch;
   f32x2 spec[SPEC];  // empty splits hold stale bytes here: only ever selected, never multiplied by 0
 #pragma unroll
-  for (int u = 0; u < SPEC; ++u) spec[u] = *reinterpret_cast<const f32x2 *>(po + (long)min(u, nsplit - 1) * D);
+  for (int u = 0; u < SPEC; ++u) spec[u] = *reinterpret_cast<const f32x2 *>(po + (long)min(k0 + u, nsplit - 1) * D);
   float M = -INFINITY;
-  for (int k = lane; k < nsplit; k += 64) M = fmaxf(M, ml[k][0]);
+  for (int k = k0 + lane; k < k1; k += 64) M = fmaxf(M, ml[k][0]);
   M = wave_max(M);
+  float a0 = 0.f, a1 = 0.f, den = 0.f;
+  if (M != -INFINITY) {
+    for (int base = k0; base < k1; base += 64) {
+      const int cnt = min(64, k1 - base);
+      float f = 0.f;
+      if (lane < cnt) {
+        f32x2 v = ml[base + lane];
+        f = __builtin_amdgcn_exp2f(v[0] - M);  // 0 for an empty split
+        den += f * v[1];
+      }
+      int k = 0;
+      if (base == k0) {
+#pragma unroll
+        for (int u = 0; u < SPEC; ++u) {
+          float fu = u < cnt ? lane_bcast(f, u) : 0.f;
+          a0 += fu != 0.f ? fu * spec[u][0] : 0.f;
+          a1 += fu != 0.f ? fu * spec[u][1] : 0.f;
+        }
+        k = SPEC;
+      }
+      for (; k + 8 <= cnt; k += 8) {  // eight independent loads in flight per lane
+        f32x2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x2 *>(po + (long)(base + k + u) * D);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          float fu = lane_bcast(f, k + u);
+          a0 += fu != 0.f ? fu * v[u][0] : 0.f;
+          a1 += fu != 0.f ? fu * v[u][1] : 0.f;
+        }
+      }
+      for (; k < cnt; ++k) {
+        float f0 = lane_bcast(f, k);
+        if (f0 != 0.f) {  // wave-uniform
+          f32x2 v0 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k) * D);
+          a0 += f0 * v0[0];
+          a1 += f0 * v0[1];
+        }
+      }
+    }
+    den = wave_sum(den);
+  }
+  if (W > 1) {
+    __shared__ float s_m[W], s_den[W], s_a[W][64][2];
+    if (lane == 0) {
+      s_m[w] = M;
+      s_den[w] = den;
+    }
+    s_a[w][lane][0] = a0;
+    s_a[w][lane][1] = a1;
+    __syncthreads();
+    if (w != 0) return;
+    float Mg = s_m[0];
+#pragma unroll
+    for (int i = 1; i < W; ++i) Mg = fmaxf(Mg, s_m[i]);
+    M = Mg;
+    a0 = a1 = den = 0.f;
+    if (Mg != -INFINITY) {
+#pragma unroll
+      for (int i = 0; i < W; ++i) {
+        const float f = __builtin_amdgcn_exp2f(s_m[i] - Mg);  // 0 for a wave whose range was empty
+        if (f != 0.f) {
+          den += f * s_den[i];
+          a0 += f * s_a[i][lane][0];
+          a1 += f * s_a[i][lane][1];
+        }
+      }
+    }
+  }
   if (M == -INFINITY) {
     if (writer) *dst = __builtin_convertvector((f32x2){0.f, 0.f}, bf16x2);
     return;
   }
-  float a0 = 0.f, a1 = 0.f, den = 0.f;
-  for (int base = 0; base < nsplit; base += 64) {
-    const int cnt = min(64, nsplit - base);
-    float f = 0.f;
-    if (lane < cnt) {
-      f32x2 v = ml[base + lane];
-      f = __builtin_amdgcn_exp2f(v[0] - M);  // 0 for an empty split
-      den += f * v[1];
-    }
-    int k = 0;
-    if (base == 0) {
-#pragma unroll
-      for (int u = 0; u < SPEC; ++u) {
-        float fu = u < cnt ? lane_bcast(f, u) : 0.f;
-        a0 += fu != 0.f ? fu * spec[u][0] : 0.f;
-        a1 += fu != 0.f ? fu * spec[u][1] : 0.f;
-      }
-      k = SPEC;
-    }
-    for (; k + 8 <= cnt; k += 8) {  // eight independent loads in flight per lane
-      f32x2 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x2 *>(po + (long)(base + k + u) * D);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        float fu = lane_bcast(f, k + u);
-        a0 += fu != 0.f ? fu * v[u][0] : 0.f;
-        a1 += fu != 0.f ? fu * v[u][1] : 0.f;
-      }
-    }
-    for (; k < cnt; ++k) {
-      float f0 = lane_bcast(f, k);
-      if (f0 != 0.f) {  // wave-uniform
-        f32x2 v0 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k) * D);
-        a0 += f0 * v0[0];
-        a1 += f0 * v0[1];
-      }
-    }
-  }
-  den = wave_sum(den);
   float inv = 1.0f / den;
   if (writer) *dst = __builtin_convertvector((f32x2){a0 * inv, a1 * inv}, bf16x2);
+}
+
+int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
+                   hipStream_t stream) {
+  if (rows <= 0) return SP_OK;
+  if (rows > 0x7fffffffL) return fail(SP_ERR_BAD_SHAPE, "combine: %ld rows exceed the grid limit", rows);
+  const bool wide = nsplit > 32;  // many splits per row: four waves share the row
+  if (head_dim == 128) {
+    if (wide) hipLaunchKernelGGL((combine_kernel<128, 4>), dim3((unsigned)rows), dim3(256), 0, stream, part_o, part_ml, (char *)out, nsplit);
+    else hipLaunchKernelGGL((combine_kernel<128, 1>), dim3((unsigned)rows), dim3(64), 0, stream, part_o, part_ml, (char *)out, nsplit);
+  } else {
+    if (wide) hipLaunchKernelGGL((combine_kernel<64, 4>), dim3((unsigned)rows), dim3(256), 0, stream, part_o, part_ml, (char *)out, nsplit);
+    else hipLaunchKernelGGL((combine_kernel<64, 1>), dim3((unsigned)rows), dim3(64), 0, stream, part_o, part_ml, (char *)out, nsplit);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SP_ERR_HIP, "combine launch: %s", hipGetErrorString(e));
+  return SP_OK;
 }
 
 template <int D, int NB>
@@ -413,11 +465,7 @@ static int launch_decode_d(DecodeArgs &a, char *out, int batch, hipStream_t stre
   if (rc != SP_OK) return rc;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "decode split launch: %s", hipGetErrorString(e));
-  hipLaunchKernelGGL(decode_combine_kernel<D>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o, a.part_ml, out,
-                     a.nsplit);
-  e = hipGetLastError();
-  if (e != hipSuccess) return fail(SP_ERR_HIP, "decode combine launch: %s", hipGetErrorString(e));
-  return SP_OK;
+  return launch_combine(a.part_o, a.part_ml, out, (long)batch * a.Hq, a.nsplit, D, stream);
 }
 
 int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
@@ -443,19 +491,7 @@ int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_
   a.tau = 8.0f / a.sl2e;
   if (max_seq_len <= 0) {
     // every sequence is empty: the combine kernel alone writes the zero rows
-    a.chunk = kDecMinChunk;
-    a.nsplit = 1;
-    a.part_o = nullptr;
-    a.part_ml = nullptr;
-    if (c.head_dim == 128)
-      hipLaunchKernelGGL(decode_combine_kernel<128>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o,
-                         a.part_ml, (char *)out, a.nsplit);
-    else
-      hipLaunchKernelGGL(decode_combine_kernel<64>, dim3(batch * a.Hq), dim3(64), 0, stream, a.part_o,
-                         a.part_ml, (char *)out, a.nsplit);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(SP_ERR_HIP, "decode combine launch: %s", hipGetErrorString(e));
-    return SP_OK;
+    return launch_combine(nullptr, nullptr, out, (long)batch * num_q_heads, 1, c.head_dim, stream);
   }
   a.chunk = pick_chunk(batch, num_q_heads, max_seq_len);
   a.nsplit = (max_seq_len + a.chunk - 1) / a.chunk;

@@ -54,6 +54,10 @@ struct PrefillArgs {
   int max_pages, num_pages, Hq, Hkv, gshift, n_hgroups, ntiles_x;
   float sl2e;  // scale * log2(e)
   float tau;   // lazy-rescale threshold in raw score units (8 / sl2e)
+  // PART kernels: blockIdx.z of kv_splits workgroups share a query tile's key range and write
+  // un-normalised partials [row][kv_splits][D] and (max in log2 units, sum) [row][kv_splits][2]
+  float *part_o, *part_ml;
+  int kv_splits;
 };
 
 // The waves form two groups of four, one wave of each group per SIMD (waves w and w+4 share a
@@ -84,7 +88,12 @@ struct PrefillArgs {
 // stream in its own LDS region), so the critical path of the longest work item halves while
 // the ping-pong stays intact; the two running states are merged through LDS at the end like
 // the splits of the decode path.
-template <int D, int KVT, int PFD, bool SPLIT>
+//
+// PART = true additionally cuts a query tile's key range into kv_splits contiguous pieces, one
+// workgroup each (blockIdx.z), which write un-normalised partials for the combine pass: the way
+// out when a batch has few query tokens on long cached prefixes (late chunks of a chunked
+// prefill), where one workgroup per query tile would walk thousands of keys alone.
+template <int D, int KVT, int PFD, bool SPLIT, bool PART>
 __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   using G = TileGeom<D>;
   using Z = SwzTile<D>;
@@ -104,10 +113,14 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   const int grp = w >> 2;  // wave-uniform; waves w and w+4 share a SIMD: one wave of each group per SIMD
   const int wq = w & 3;    // wave inside its group
   const int rb = SPLIT ? grp * REGION : 0;  // this group's tile buffers
-  auto gtile = [&](int i) { return SPLIT ? 2 * i + grp : i; };  // local tile number -> key tile of the sequence
   // Workgroups are dispatched in blockIdx.x-major order: the longest key ranges of ALL sequences
   // go first, the short ones fill in behind them.
-  const int seq = blockIdx.x / a.n_hgroups, hg = blockIdx.x - seq * a.n_hgroups;
+  // Consecutive workgroup ids go round-robin over the 8 XCDs; with the (sequence, head group)
+  // index rotated by the tile index, the workgroups of one sequence spread over all XCDs even
+  // when the batch size is a multiple of 8 (unrotated, each sequence would sit on one XCD and a
+  // batch of unequal lengths would leave most of the chip idle).
+  const int sh = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
+  const int seq = sh / a.n_hgroups, hg = sh - seq * a.n_hgroups;
   const int tile = a.ntiles_x - 1 - (int)blockIdx.y;
   const int tpt = COLS >> a.gshift;
   const int q0 = a.cu_q[seq];
@@ -150,13 +163,27 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // A column of the second SPLIT group may see only masked keys in its first tiles, or none at
   // all: its running max starts at a large finite value so that "all masked" gives weights
   // exp2(-inf) = 0 instead of exp2(-inf + inf).  Tile 0 always holds a visible key otherwise.
-  float m_used = SPLIT ? -1e30f : -INFINITY, l = 0.f;
+  float m_used = (SPLIT || PART) ? -1e30f : -INFINITY, l = 0.f;
   f32x16 sacc[KB];
   bf16x8 pop[KB][2];
 
-  const int T = (kv_end + KVT - 1) / KVT;           // key tiles this workgroup walks
-  const int Tl = SPLIT ? (T - grp + 1) / 2 : T;      // ... of which this group computes on
-  const int P = SPLIT ? (T + 1) / 2 : T;             // tile periods (= barriers) of the workgroup
+  // key tiles [t_begin, T) of the query tile's range belong to this workgroup
+  const int T_all = (kv_end + KVT - 1) / KVT;
+  int t_begin = 0, T = T_all;
+  if (PART) {
+    const int per = (T_all + a.kv_splits - 1) / a.kv_splits;
+    t_begin = (int)blockIdx.z * per;
+    T = min(T_all, t_begin + per);
+  }
+  const long prow = ((long)(q0 + token) * a.Hq + head) * a.kv_splits + (PART ? (int)blockIdx.z : 0);  // partial slot
+  if (PART && t_begin >= T) {  // nothing left for this piece: an empty partial
+    if (valid && half == 0) *reinterpret_cast<f32x2 *>(a.part_ml + prow * 2) = (f32x2){-INFINITY, 0.f};
+    return;
+  }
+  const int ntl = T - t_begin;
+  const int Tl = SPLIT ? (ntl - grp + 1) / 2 : ntl;  // tiles this group computes on
+  const int P = SPLIT ? (ntl + 1) / 2 : ntl;         // tile periods (= barriers) of the workgroup
+  auto gtile = [&](int i) { return t_begin + (SPLIT ? 2 * i + grp : i); };  // local tile number -> key tile of the sequence
 
   // ---- tile loads, all issued by the first group during its MFMA phase (the one phase that
   // starts right after a barrier AND has issue slots to spare; the same instructions placed in
@@ -171,7 +198,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int NLD = NSTREAM * 2 * NIW;  // load instructions per wave and period
   const int last_kv = kv_end - 1, last_page = last_kv >> 4;
   const int dq = lane >> 4, dslot = lane & 15;
-  auto stream_tile = [&](int g, int i) { return SPLIT ? 2 * i + g : i; };  // local tile i of stream g
+  auto stream_tile = [&](int g, int i) { return t_begin + (SPLIT ? 2 * i + g : i); };  // local tile i of stream g
   // The inline assembly below makes the compiler treat every later load as possibly clobbered,
   // so block-table reads are vector loads; the value stays in a VGPR until the load that needs
   // it is issued one period later, and only then moves to an SGPR.
@@ -469,10 +496,24 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[db][r] = o[db][r] * fa + xch[(16 * db + r) * 256] * fb;
+    m_used = m_new;  // what l and o now refer to (a partial carries it along)
   }
 
-  // ---- normalise and store
   float lt = l + other_half(l);
+  if (PART) {  // un-normalised partial for the combine pass
+    if (valid) {
+      float *po = a.part_o + prow * D;
+#pragma unroll
+      for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * r4 + 4 * half) =
+              (f32x4){o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
+      if (half == 0) *reinterpret_cast<f32x2 *>(a.part_ml + prow * 2) = (f32x2){m_used * a.sl2e, lt};
+    }
+    return;
+  }
+  // ---- normalise and store
   float inv = 1.0f / lt;
   if (valid) {
     char *dst = a.out + out_off;
@@ -486,9 +527,27 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 }
 
 static int g_split_mode = 0;
+static int g_kv_splits = 0;
 void set_prefill_split(int mode) { g_split_mode = mode; }
+void set_prefill_kv_splits(int n) { g_kv_splits = n; }
 
 typedef void (*prefill_fn)(PrefillArgs);
+
+constexpr int kMaxKvSplits = 16;
+constexpr long kMaxPartialSlots = 1L << 17;  // (row, split) pairs the workspace is ever sized for
+
+// Largest number of key-range pieces a batch of `rows` (token, head) rows may be cut into.
+static int kv_split_cap(long rows) {
+  if (rows <= 0) return 1;
+  long cap = kMaxPartialSlots / rows;
+  return (int)(cap < 1 ? 1 : cap > kMaxKvSplits ? kMaxKvSplits : cap);
+}
+
+size_t prefill_workspace_bytes(int total_q_tokens, int num_q_heads, int head_dim) {
+  const long rows = (long)total_q_tokens * num_q_heads;
+  const int cap = kv_split_cap(rows);
+  return cap >= 2 ? (size_t)rows * cap * (head_dim + 2) * sizeof(float) : 0;
+}
 
 // Launches one prefill kernel instantiation with `cols` query columns per workgroup.
 static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, const PrefillArgs &a0, int batch,
@@ -504,18 +563,29 @@ static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, cons
   long gx = (long)batch * a.n_hgroups;
   if (gx > 0x7fffffffL || a.ntiles_x > 65535)
     return fail(SP_ERR_BAD_SHAPE, "sp_attn_prefill: grid %ld x %d exceeds the launch limits", gx, a.ntiles_x);
-  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)a.ntiles_x), dim3(512), smem, stream, a);
+  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)a.ntiles_x, (unsigned)a.kv_splits), dim3(512), smem, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill launch: %s", hipGetErrorString(e));
   return SP_OK;
 }
 
+template <int D>
+static int launch_prefill_d(const PrefillArgs &a, bool split, int batch, int max_q_len, hipStream_t stream) {
+  constexpr int KVT = 64, PFD = 4;
+  constexpr size_t smem = 4 * (size_t)KVT * D * 2;  // K[2] V[2], unpadded
+  static bool set[4] = {false, false, false, false};
+  if (a.kv_splits > 1) {
+    if (split) return launch_cfg(prefill_kernel<D, KVT, PFD, true, true>, &set[0], 2 * smem, 128, a, batch, max_q_len, stream);
+    return launch_cfg(prefill_kernel<D, KVT, PFD, false, true>, &set[1], smem, 256, a, batch, max_q_len, stream);
+  }
+  if (split) return launch_cfg(prefill_kernel<D, KVT, PFD, true, false>, &set[2], 2 * smem, 128, a, batch, max_q_len, stream);
+  return launch_cfg(prefill_kernel<D, KVT, PFD, false, false>, &set[3], smem, 256, a, batch, max_q_len, stream);
+}
+
 int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                    int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
-                   hipStream_t stream) {
-  (void)total_q;
-  (void)max_kv_len;
+                   void *workspace, size_t workspace_bytes, hipStream_t stream) {
   PrefillArgs a;
   a.k_pages = (const char *)c.k_pages;
   a.v_pages = (const char *)c.v_pages;
@@ -539,24 +609,44 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   a.ntiles_x = 0;
   a.sl2e = scale * 1.44269504088896340736f;
   a.tau = 8.0f / a.sl2e;
-  constexpr int KVT = 64, PFD = 4;
-  static bool set[4] = {false, false, false, false};
-  // No more 256-column workgroups than CUs: let the two wave groups split the key range of 128
-  // columns instead (halves the critical path of the longest work item; measured faster up to
-  // that grid size, slower beyond it because every K/V tile is then staged for half the columns).
-  int tpt256 = 256 >> gshift;
-  long wgs256 = (long)((max_q_len + tpt256 - 1) / tpt256) * batch * a.n_hgroups;
-  const bool small_grid = g_split_mode == 0 ? wgs256 <= 256 : g_split_mode == 2;
-  if (c.head_dim == 128) {
-    size_t smem = 4 * (size_t)KVT * 128 * 2;  // K[2] V[2], unpadded
-    if (small_grid)
-      return launch_cfg(prefill_kernel<128, KVT, PFD, true>, &set[0], 2 * smem, 128, a, batch, max_q_len, stream);
-    return launch_cfg(prefill_kernel<128, KVT, PFD, false>, &set[1], smem, 256, a, batch, max_q_len, stream);
+
+  // ---- shape of the launch, from host-side counts only.  wg128 estimates the 128-column
+  // workgroups that find work (rows / 128 plus half a partial tile per sequence and head group).
+  const long rows = (long)total_q * num_q_heads;
+  const long wg128 = rows / 128 + ((long)batch * a.n_hgroups + 1) / 2;
+  // Up to about one 256-column workgroup per CU: let the two wave groups split the key range of
+  // 128 columns instead (halves the critical path of the longest work item; measured faster up
+  // to that grid size, slower beyond it because every K/V tile is then staged for half the
+  // columns).
+  const bool small_grid = g_split_mode == 0 ? wg128 <= 576 : g_split_mode == 2;
+  // How many pieces the key range of a query tile is cut into (1 = none): only when even the
+  // 128-column workgroups leave most CUs idle and the key ranges are long, and bounded by what
+  // the caller's workspace holds.  A piece's partial costs about as much HBM time as 500 keys
+  // cost matrix time, so pieces stay around 1500 keys or longer.
+  const size_t slot_bytes = (size_t)(c.head_dim + 2) * sizeof(float);
+  int kvs = 1;
+  if (workspace && rows > 0) {
+    if (g_kv_splits > 0) {
+      kvs = g_kv_splits;
+    } else if (small_grid) {
+      const long by_grid = 256 / (wg128 > 0 ? wg128 : 1);
+      const long by_len = (long)max_kv_len / 1536;
+      kvs = (int)(by_grid < by_len ? by_grid : by_len);
+    }
+    const int cap = kv_split_cap(rows);
+    if (kvs > cap) kvs = cap;
+    const size_t fit = workspace_bytes / ((size_t)rows * slot_bytes);
+    if ((size_t)kvs > fit) kvs = (int)fit;
+    if (kvs < 1) kvs = 1;
   }
-  size_t smem = 4 * (size_t)KVT * 64 * 2;
-  if (small_grid)
-    return launch_cfg(prefill_kernel<64, KVT, PFD, true>, &set[2], 2 * smem, 128, a, batch, max_q_len, stream);
-  return launch_cfg(prefill_kernel<64, KVT, PFD, false>, &set[3], smem, 256, a, batch, max_q_len, stream);
+  a.kv_splits = kvs;
+  a.part_o = (float *)workspace;
+  a.part_ml = a.part_o + (size_t)rows * kvs * c.head_dim;
+
+  int rc = c.head_dim == 128 ? launch_prefill_d<128>(a, small_grid, batch, max_q_len, stream)
+                             : launch_prefill_d<64>(a, small_grid, batch, max_q_len, stream);
+  if (rc != SP_OK || kvs == 1) return rc;
+  return launch_combine(a.part_o, a.part_ml, out, rows, kvs, c.head_dim, stream);
 }
 
 }  // namespace sp

@@ -32,12 +32,20 @@ int launch_kv_append(const sp_cache_desc &c, const void *k_new, const void *v_ne
 int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                    int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
-                   hipStream_t stream);
+                   void *workspace, size_t workspace_bytes, hipStream_t stream);
+size_t prefill_workspace_bytes(int total_q_tokens, int num_q_heads, int head_dim);
 
 // Tuning hooks behind sp_debug_set_tuning (0 restores the built-in heuristic).
 void set_decode_chunk(int chunk);
 void set_decode_ring(int slots);   // LDS ring depth of the decode split kernel: 0 heuristic, 2..4
+void set_prefill_kv_splits(int n);  // pieces a query tile's key range is cut into: 0 heuristic, 1..16
 void set_prefill_split(int mode);  // 0 heuristic, 1 never split the key range over the wave groups, 2 always
+
+// Log-sum-exp merge of per-split partials: part_o [rows][nsplit][head_dim] fp32 un-normalised,
+// part_ml [rows][nsplit][2] fp32 (max in log2 units, sum); out [rows][head_dim] bf16.
+// part_o == nullptr writes zero rows.
+int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
+                   hipStream_t stream);
 
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);
 int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,

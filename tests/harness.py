@@ -38,6 +38,7 @@ class GpuRunner:
         self.cache = sp.KVCache.empty(w.num_pages, w.Hkv, w.d, fill_bits=W.CANARY)
         self.bt = dev_i32(w.block_table)
         self.ws = None
+        self.prefill_workspace = True   # hand sp_attn_prefill the scratch that lets it split key ranges
 
     def append(self, st: W.Step):
         self.sp.sp_kv_append(self.cache, to_dev(st.k_new), to_dev(st.v_new), dev_i32(st.cu_new),
@@ -50,8 +51,10 @@ class GpuRunner:
         q = to_dev(st.q)
         out = torch.empty_like(q)
         if st.kind == "prefill":
+            need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], w.Hq, w.d) if self.prefill_workspace else 0
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
             sp.sp_attn_prefill(self.cache, q, out, dev_i32(st.cu_new), dev_i32(st.ctx_lens), self.bt,
-                               int(st.new_lens.max()), int(st.seq_lens.max()), float(w.scale))
+                               int(st.new_lens.max()), int(st.seq_lens.max()), float(w.scale), workspace=ws)
         else:
             seq_lens = st.seq_lens
             mx = int(seq_lens.max())

@@ -62,6 +62,19 @@ def test_workspace_size_is_host_only_arithmetic(built_lib):
     assert f(1, 1, 8, 128) >= 8 * 130 * 4
 
 
+def test_prefill_workspace_size_is_host_only_arithmetic(built_lib):
+    f = built_lib.sp_attn_prefill_workspace_size
+    f.restype = ctypes.c_size_t
+    f.argtypes = [ctypes.c_int32] * 4
+    assert f(4, 0, 8, 128) == 0
+    # few query rows: room for up to 16 pieces of (head_dim + 2) fp32 per (token, head)
+    assert f(4, 100, 8, 128) == 100 * 8 * 16 * 130 * 4
+    # many query rows: key ranges are never cut, no workspace asked for
+    assert f(4, 32768, 8, 128) == 0
+    small, big = f(1, 1000, 8, 128), f(1, 8000, 8, 128)
+    assert small > 0 and big > 0 and big <= 2 * (1 << 17) * 130 * 4
+
+
 def test_argument_validation_needs_no_gpu(built_lib):
     """Validation happens before any HIP call, so these return codes are checkable on a CPU machine."""
     import paper_2507_11830_amd as sp
@@ -105,5 +118,7 @@ def test_tuning_keys_are_validated(built_lib):
         assert L.sp_debug_set_tuning(b"prefill_split", v) == want
     for v, want in [(2, sp.SP_OK), (4, sp.SP_OK), (1, sp.SP_ERR_UNSUPPORTED), (5, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"decode_ring", v) == want
-    for key in (b"decode_chunk", b"decode_ring", b"prefill_split"):
+    for v, want in [(1, sp.SP_OK), (16, sp.SP_OK), (17, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
+        assert L.sp_debug_set_tuning(b"prefill_kv_splits", v) == want
+    for key in (b"decode_chunk", b"decode_ring", b"prefill_split", b"prefill_kv_splits"):
         assert L.sp_debug_set_tuning(key, 0) == sp.SP_OK

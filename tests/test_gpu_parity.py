@@ -110,6 +110,52 @@ def test_prefill_both_wave_group_modes(mode, Hq, Hkv, d):
         sp.sp_debug_set_tuning("prefill_split", 0)
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("pieces", [2, 3, 16])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 1, 128), (4, 2, 64)])
+def test_prefill_key_range_cut_into_pieces(mode, pieces, Hq, Hkv, d):
+    """With a workspace sp_attn_prefill may cut key ranges into pieces merged by the combine pass;
+    forced here for every piece count class (more pieces than tiles included, so empty pieces and
+    pieces whose keys are all masked for some rows occur), in both wave-group modes."""
+    import paper_2507_11830_amd as sp
+
+    lens = [1, 17, 64, 65, 129, 300, 0, 700, 1500]
+    ctx = [0, 5, 31, 64, 100, 111, 0, 689, 1490]
+    sp.sp_debug_set_tuning("prefill_split", mode)
+    sp.sp_debug_set_tuning("prefill_kv_splits", pieces)
+    try:
+        run_full_compare(custom_workload(f"pieces-{mode}-{pieces}-{Hq}-{Hkv}-{d}", lens, ctx, Hq, Hkv, d, "prefill", seed=71))
+    finally:
+        sp.sp_debug_set_tuning("prefill_split", 0)
+        sp.sp_debug_set_tuning("prefill_kv_splits", 0)
+
+
+def test_prefill_without_workspace_matches_with_workspace():
+    """The workspace is optional: without it the same call computes every key range in one piece."""
+    w = custom_workload("no-ws", [600, 40, 2100], [580, 0, 2000], 8, 1, 128, "prefill", seed=72)
+    outs = []
+    for use_ws in (True, False):
+        g = GpuRunner(w)
+        g.prefill_workspace = use_ws
+        for st in w.steps():
+            g.append(st)
+            if st.kind == "prefill":
+                outs.append(W.bf16_bits_to_f64(g.attend(st)))
+    o = OracleRunner(w)
+    for st in w.steps():
+        o.append(st)
+        if st.kind == "prefill":
+            want = o.attend(st)
+    assert np.abs(outs[0] - want).max() <= TOL and np.abs(outs[1] - want).max() <= TOL
+
+
+def test_decode_single_long_sequence_many_splits():
+    """One 20000-token sequence: more than 32 splits per row, so the combine pass runs its
+    four-wave form."""
+    lens = np.array([20000])
+    run_full_compare(custom_workload("decode-long-1", lens, lens - 1, 8, 1, 128, "decode", seed=73), check_cache=False)
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(16, 2), (32, 4), (64, 8)])
 def test_other_shard_shapes_of_the_sp_tp_family(Hq, Hkv):
     """Shards of an SP x TP = P factorisation with fewer GPUs hold several KV heads each; the same
