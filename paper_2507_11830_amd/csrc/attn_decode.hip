@@ -88,7 +88,10 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   const int lane = threadIdx.x;
   const int col = lane & 31, half = lane >> 5;
   const int seq = blockIdx.y / a.n_hgroups, hg = blockIdx.y - seq * a.n_hgroups;
-  const int split = blockIdx.x;
+  // Consecutive workgroup ids go round-robin over the 8 XCDs; rotating the split index by the
+  // row index keeps the high splits (which only long sequences have) from piling onto the same
+  // XCDs whenever the split count is a multiple of 8.
+  const int split = (int)((blockIdx.x + blockIdx.y) % gridDim.x);
   // A split starts at a position that does not depend on the sequence length, so its page ids
   // and query rows are requested in the same memory round trip as the length itself.
   const int kv0 = split * a.chunk;  // a multiple of 32
