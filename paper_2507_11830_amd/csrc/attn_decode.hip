@@ -430,13 +430,19 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
                    hipStream_t stream) {
   if (rows <= 0) return SP_OK;
   if (rows > 0x7fffffffL) return fail(SP_ERR_BAD_SHAPE, "combine: %ld rows exceed the grid limit", rows);
-  const bool wide = nsplit > 32;  // many splits per row: four waves share the row
+  // many splits per row: several waves share the row (each wave's loop is a chain of dependent
+  // memory round trips, one per eight splits)
+  const int waves = nsplit > 128 ? 8 : nsplit > 32 ? 4 : 1;
+  const dim3 grid((unsigned)rows);
+  char *o = (char *)out;
   if (head_dim == 128) {
-    if (wide) hipLaunchKernelGGL((combine_kernel<128, 4>), dim3((unsigned)rows), dim3(256), 0, stream, part_o, part_ml, (char *)out, nsplit);
-    else hipLaunchKernelGGL((combine_kernel<128, 1>), dim3((unsigned)rows), dim3(64), 0, stream, part_o, part_ml, (char *)out, nsplit);
+    if (waves == 8) hipLaunchKernelGGL((combine_kernel<128, 8>), grid, dim3(512), 0, stream, part_o, part_ml, o, nsplit);
+    else if (waves == 4) hipLaunchKernelGGL((combine_kernel<128, 4>), grid, dim3(256), 0, stream, part_o, part_ml, o, nsplit);
+    else hipLaunchKernelGGL((combine_kernel<128, 1>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit);
   } else {
-    if (wide) hipLaunchKernelGGL((combine_kernel<64, 4>), dim3((unsigned)rows), dim3(256), 0, stream, part_o, part_ml, (char *)out, nsplit);
-    else hipLaunchKernelGGL((combine_kernel<64, 1>), dim3((unsigned)rows), dim3(64), 0, stream, part_o, part_ml, (char *)out, nsplit);
+    if (waves == 8) hipLaunchKernelGGL((combine_kernel<64, 8>), grid, dim3(512), 0, stream, part_o, part_ml, o, nsplit);
+    else if (waves == 4) hipLaunchKernelGGL((combine_kernel<64, 4>), grid, dim3(256), 0, stream, part_o, part_ml, o, nsplit);
+    else hipLaunchKernelGGL((combine_kernel<64, 1>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "combine launch: %s", hipGetErrorString(e));

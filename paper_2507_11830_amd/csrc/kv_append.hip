@@ -11,34 +11,57 @@
 
 namespace sp {
 
+// The chain of dependent memory round trips decides the time of a small append (a decode step
+// moves a few KiB): the new rows are requested first, the per-sequence prefix sums are staged
+// in LDS with one cooperative load (so the search for a token's sequence costs no further round
+// trips), and only the block-table lookup remains between them and the store.
+constexpr int kCuInLds = 2048;  // prefix sums staged in LDS; longer batches search global memory
+
 __global__ __launch_bounds__(256) void kv_append_kernel(
     u32x4 *__restrict__ k_pages, u32x4 *__restrict__ v_pages, const u32x4 *__restrict__ k_new,
     const u32x4 *__restrict__ v_new, const int32_t *__restrict__ cu_new,
     const int32_t *__restrict__ ctx_lens, const int32_t *__restrict__ block_table, int batch,
     int max_pages, int num_pages, int chunks_per_head, int num_kv_heads, long total_chunks) {
-  long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= total_chunks) return;
-  int chunks_per_token = chunks_per_head * num_kv_heads;
-  int tok = (int)(gid / chunks_per_token);
-  int rem = (int)(gid - (long)tok * chunks_per_token);
-  int g = rem / chunks_per_head;
-  int c = rem - g * chunks_per_head;
+  __shared__ int32_t s_cu[kCuInLds];
+  const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = gid < total_chunks;
+  u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+  if (live) {
+    kv = __builtin_nontemporal_load(k_new + gid);
+    vv = __builtin_nontemporal_load(v_new + gid);
+  }
+  const bool staged = batch + 1 <= kCuInLds;
+  if (staged) {
+    for (int i = threadIdx.x; i <= batch; i += blockDim.x) s_cu[i] = cu_new[i];
+    __syncthreads();
+  }
+  if (!live) return;
+  const int chunks_per_token = chunks_per_head * num_kv_heads;
+  const int tok = (int)(gid / chunks_per_token);
+  const int rem = (int)(gid - (long)tok * chunks_per_token);
+  const int g = rem / chunks_per_head;
+  const int c = rem - g * chunks_per_head;
 
   // Largest s with cu_new[s] <= tok (sequences with no new tokens are skipped over).
   int lo = 0, hi = batch;
-  while (hi - lo > 1) {
-    int mid = (lo + hi) >> 1;
-    if (cu_new[mid] <= tok) lo = mid; else hi = mid;
+  if (staged) {
+    while (hi - lo > 1) {
+      int mid = (lo + hi) >> 1;
+      if (s_cu[mid] <= tok) lo = mid; else hi = mid;
+    }
+  } else {
+    while (hi - lo > 1) {
+      int mid = (lo + hi) >> 1;
+      if (cu_new[mid] <= tok) lo = mid; else hi = mid;
+    }
   }
-  int s = lo;
-  int pos = ctx_lens[s] + (tok - cu_new[s]);
-  int logical = pos >> 4;
+  const int s = lo;
+  const int pos = ctx_lens[s] + (tok - (staged ? s_cu[s] : cu_new[s]));
+  const int logical = pos >> 4;
   if (pos < 0 || logical >= max_pages) return;
-  int page = block_table[(long)s * max_pages + logical];
+  const int page = block_table[(long)s * max_pages + logical];
   if (page < 0 || page >= num_pages) return;  // bad metadata must not turn into a wild store
-  long dst = (((long)page * num_kv_heads + g) * kPage + (pos & 15)) * chunks_per_head + c;
-  u32x4 kv = __builtin_nontemporal_load(k_new + gid);
-  u32x4 vv = __builtin_nontemporal_load(v_new + gid);
+  const long dst = (((long)page * num_kv_heads + g) * kPage + (pos & 15)) * chunks_per_head + c;
   k_pages[dst] = kv;
   v_pages[dst] = vv;
 }

@@ -149,11 +149,12 @@ def test_prefill_without_workspace_matches_with_workspace():
     assert np.abs(outs[0] - want).max() <= TOL and np.abs(outs[1] - want).max() <= TOL
 
 
-def test_decode_single_long_sequence_many_splits():
-    """One 20000-token sequence: more than 32 splits per row, so the combine pass runs its
-    four-wave form."""
-    lens = np.array([20000])
-    run_full_compare(custom_workload("decode-long-1", lens, lens - 1, 8, 1, 128, "decode", seed=73), check_cache=False)
+@pytest.mark.parametrize("length", [5000, 20000])
+def test_decode_single_long_sequence_many_splits(length):
+    """One long sequence: 40 resp. 157 splits per row, so the combine pass runs its four- resp.
+    eight-wave form."""
+    lens = np.array([length])
+    run_full_compare(custom_workload(f"decode-long-{length}", lens, lens - 1, 8, 1, 128, "decode", seed=73), check_cache=False)
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(16, 2), (32, 4), (64, 8)])
