@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
 # what the same counters read for the 1 GiB copy of `--workload copy` (FETCH_SIZE x2.000,
 # WRITE_SIZE x1.000); figures and commands in profiles/pmc_hbm_traffic_and_mfma.md.
-TRAFFIC_PREFILL_C2 = int(23822.3 * 1024 * 2.0 + 16384.0 * 1024)
-TRAFFIC_DECODE_C3 = int((67874.9 + 639.5) * 1024 * 2.0 + (1241.0 + 128.0) * 1024)
+TRAFFIC_PREFILL_C2 = int(17273.9 * 1024 * 2.0 + 16384.1 * 1024)
+TRAFFIC_DECODE_C3 = int((68103.8 + 4190.5) * 1024 * 2.0 + (4849.8 + 128.0) * 1024)
 
 
 def _dev_bf16(u16):
@@ -403,7 +403,7 @@ def main():
                      "algorithmic_flops": pre.flops},
         "roofline_decode": {"bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": gbps / PEAK_HBM_GBPS, "traffic": TRAFFIC_DECODE_C3,
-                            "kernel": "decode_split_kernel + decode_combine_kernel"},
+                            "kernel": "decode_split_kernel + combine_kernel"},
     }
     if not args.no_extras:
         ceil = ceilings(sp)
