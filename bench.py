@@ -119,6 +119,11 @@ class DecodeJob:
         self.sp.sp_attn_decode(cache, self.q, self.out, self.seq_lens, self.bt, self.max_len,
                                float(self.w.scale), self.ws)
 
+    def fused_step(self, cache):
+        """Append + decode in one call (the append runs inside the attention kernel)."""
+        self.sp.sp_decode_step(cache, self.k, self.v, self.q, self.out, self.seq_lens, self.bt, self.max_len,
+                               float(self.w.scale), self.ws)
+
 
 def time_phases(fns, steps, warmup):
     """Runs the phase functions in order `steps` times; returns (wall ms/step, [mean ms per phase])."""
@@ -295,9 +300,19 @@ def extra_shift_decode(sp, steps=64):
         state["t"] = (t + 1) % steps
 
     _, per = time_phases([app, att], steps, 4)
+
+    def fused():
+        t = state["t"]
+        sp.sp_decode_step(cache, k[T + t:T + t + 1], v[T + t:T + t + 1], q[t:t + 1], out, lens[t], bt, T + steps,
+                          float(w.scale), ws)
+        state["t"] = (t + 1) % steps
+
+    state["t"] = 0
+    _, per_f = time_phases([fused], steps, 4)
     nbytes = W.decode_bytes(np.array([T + steps // 2]), 8, 1, 128)
     return {"workload": f"C5b decode steps on the cache the 32768-token prefill filled (same block table, no re-layout), "
                         f"{steps} steps", "us_per_step_attn": per[1] * 1e3, "us_per_step_kv_append": per[0] * 1e3,
+            "us_per_step_fused": per_f[0] * 1e3,
             "GBps_cache_resident": nbytes / per[1] / 1e6}
 
 
@@ -405,6 +420,11 @@ def main():
                             "frac": gbps / PEAK_HBM_GBPS, "traffic": TRAFFIC_DECODE_C3,
                             "kernel": "decode_split_kernel + combine_kernel"},
     }
+    _, per_f = time_phases([lambda: dec.fused_step(dec.next_cache())], args.steps, args.warmup)
+    res["decode_step_fused"] = {"ms": per_f[0], "GBps": dec.bytes / per_f[0] / 1e6,
+                                "separate_append_plus_decode_ms": t_app_d + t_dec,
+                                "note": "sp_decode_step: same work as kv_append_decode + attn_decode in two launches "
+                                        "instead of three"}
     if not args.no_extras:
         ceil = ceilings(sp)
         res["ceilings"] = ceil

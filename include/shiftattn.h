@@ -118,6 +118,25 @@ int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out,
                    int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads,
                    float scale, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * sp_decode_step — one decode step in one call: sp_kv_append of one new token per sequence
+ * followed by sp_attn_decode, with the append done inside the attention kernel (the step in
+ * front of the TP-mode attention fused into it; a decode step is launch-bound, and this removes
+ * one of its launches).
+ *   k_new, v_new    bf16 [batch][num_kv_heads][head_dim]: the new token's K/V of every sequence
+ *   seq_lens        int32 [batch] INCLUDING the new token, which goes to position
+ *                   seq_lens[s] - 1 (its page must be present in the block table); a sequence
+ *                   with seq_lens[s] == 0 appends nothing and gets an all-zero output row
+ *   everything else as in sp_attn_decode, same workspace size.
+ * Afterwards the cache holds the new rows exactly as sp_kv_append would have written them and
+ * `out` equals what sp_attn_decode would return on that cache.
+ */
+int sp_decode_step(const sp_cache_desc *cache, const void *k_new, const void *v_new,
+                   const void *q, void *out, const int32_t *seq_lens,
+                   const int32_t *block_table, int32_t batch, int32_t max_pages_per_seq,
+                   int32_t max_seq_len, int32_t num_q_heads, float scale, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
 /* Bytes of workspace for the given host-side shape: what sp_attn_decode requires, and what lets
  * sp_attn_prefill split key ranges (0 when the batch has too many query rows for that to pay). */
 size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens,

@@ -23,7 +23,7 @@ SP_ERR_WORKSPACE = -4
 SP_ERR_HIP = -5
 
 EXPORTS = (
-    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_attn_prefill_workspace_size",
+    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_decode_step", "sp_attn_prefill_workspace_size",
     "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_set_tuning",
     "sp_debug_ceiling_mfma", "sp_debug_ceiling_stream", "sp_status_string",
     "sp_last_error", "sp_version",
@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.sp_attn_prefill.restype = ctypes.c_int
         L.sp_attn_decode.argtypes = [cd, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, sz, vp]
         L.sp_attn_decode.restype = ctypes.c_int
+        L.sp_decode_step.argtypes = [cd, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, sz, vp]
+        L.sp_decode_step.restype = ctypes.c_int
         L.sp_attn_prefill_workspace_size.argtypes = [i32, i32, i32, i32]
         L.sp_attn_prefill_workspace_size.restype = sz
         L.sp_attn_decode_workspace_size.argtypes = [i32, i32, i32, i32]
@@ -179,6 +181,18 @@ def sp_attn_decode(cache: KVCache, q, out, seq_lens, block_table, max_seq_len: i
     _check(lib().sp_attn_decode(ctypes.byref(cache.desc), _ptr(q), _ptr(out), _ptr(seq_lens),
                                 _ptr(block_table), batch, max_pages, max_seq_len, num_q_heads, float(scale),
                                 _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def sp_decode_step(cache: KVCache, k_new, v_new, q, out, seq_lens, block_table, max_seq_len: int, scale: float,
+                   workspace, stream=None) -> None:
+    """Fused append + decode: k_new, v_new bf16 [B, Hkv, d] (the new token of every sequence),
+    seq_lens include it; the rest as sp_attn_decode."""
+    batch, max_pages = block_table.shape
+    num_q_heads = q.shape[1]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sp_decode_step(ctypes.byref(cache.desc), _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(out),
+                                _ptr(seq_lens), _ptr(block_table), batch, max_pages, max_seq_len, num_q_heads,
+                                float(scale), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
 def sp_debug_validate_metadata(cache: KVCache, seq_lens, block_table) -> None:

@@ -88,25 +88,42 @@ int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
                         workspace_bytes ? workspace : nullptr, workspace_bytes, (hipStream_t)stream);
 }
 
-int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out, const int32_t *seq_lens,
-                   const int32_t *block_table, int32_t batch, int32_t max_pages_per_seq,
-                   int32_t max_seq_len, int32_t num_q_heads, float scale, void *workspace,
-                   size_t workspace_bytes, void *stream) {
+static int decode_common(const char *name, const sp_cache_desc *cache, const void *k_new, const void *v_new,
+                         const void *q, void *out, const int32_t *seq_lens, const int32_t *block_table,
+                         int32_t batch, int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads,
+                         float scale, void *workspace, size_t workspace_bytes, void *stream) {
   if (int rc = check_cache(cache)) return rc;
   if (int rc = check_heads(cache, num_q_heads)) return rc;
   if (int rc = check_scale(scale)) return rc;
   if (batch < 0 || max_pages_per_seq < 0 || max_seq_len < 0)
-    return fail(SP_ERR_BAD_SHAPE, "negative count in sp_attn_decode");
+    return fail(SP_ERR_BAD_SHAPE, "negative count in %s", name);
   if (batch == 0) return SP_OK;
-  if (!q || !out || !seq_lens || !block_table) return fail(SP_ERR_NULL, "sp_attn_decode: NULL argument");
+  if (!q || !out || !seq_lens || !block_table) return fail(SP_ERR_NULL, "%s: NULL argument", name);
   if (max_pages_per_seq == 0 && max_seq_len > 0)
     return fail(SP_ERR_BAD_SHAPE, "max_pages_per_seq=0 with max_seq_len=%d", max_seq_len);
   size_t need = decode_workspace_bytes(batch, max_seq_len, num_q_heads, cache->head_dim);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(SP_ERR_WORKSPACE, "decode workspace: need %zu bytes, got %zu", need,
                 workspace ? workspace_bytes : (size_t)0);
-  return launch_decode(*cache, q, out, seq_lens, block_table, batch, max_pages_per_seq, max_seq_len,
-                       num_q_heads, scale, workspace, workspace_bytes, (hipStream_t)stream);
+  return launch_decode(*cache, k_new, v_new, q, out, seq_lens, block_table, batch, max_pages_per_seq,
+                       max_seq_len, num_q_heads, scale, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out, const int32_t *seq_lens,
+                   const int32_t *block_table, int32_t batch, int32_t max_pages_per_seq,
+                   int32_t max_seq_len, int32_t num_q_heads, float scale, void *workspace,
+                   size_t workspace_bytes, void *stream) {
+  return decode_common("sp_attn_decode", cache, nullptr, nullptr, q, out, seq_lens, block_table, batch,
+                       max_pages_per_seq, max_seq_len, num_q_heads, scale, workspace, workspace_bytes, stream);
+}
+
+int sp_decode_step(const sp_cache_desc *cache, const void *k_new, const void *v_new, const void *q, void *out,
+                   const int32_t *seq_lens, const int32_t *block_table, int32_t batch,
+                   int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads, float scale,
+                   void *workspace, size_t workspace_bytes, void *stream) {
+  if (batch > 0 && (!k_new || !v_new)) return fail(SP_ERR_NULL, "sp_decode_step: NULL k_new / v_new");
+  return decode_common("sp_decode_step", cache, k_new, v_new, q, out, seq_lens, block_table, batch,
+                       max_pages_per_seq, max_seq_len, num_q_heads, scale, workspace, workspace_bytes, stream);
 }
 
 size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens, int32_t num_q_heads,

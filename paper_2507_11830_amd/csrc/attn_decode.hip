@@ -26,6 +26,7 @@ constexpr int kDecMaxChunk = 1024;  // <= 64 pages per wave: one lane holds each
 
 struct DecodeArgs {
   const char *k_pages, *v_pages, *q;
+  const char *k_new, *v_new;  // APPEND kernels: this step's K/V rows, bf16 [batch][Hkv][D]
   const int32_t *seq_lens, *block_table;
   float *part_o;   // [batch][Hq][nsplit][D]
   float *part_ml;  // [batch][Hq][nsplit][2]  (m in log2 units, l)
@@ -65,13 +66,26 @@ size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int h
 // s_waitcnt that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and
 // 15:14, expcnt and lgkmcnt left at their maxima).  The "memory" clobber keeps the compiler from
 // moving LDS reads of the awaited block above it.
+// Orders a wave's own LDS writes before its later LDS reads without a workgroup barrier: the
+// hardware runs one wave's LDS operations in order, so only the compiler has to be stopped from
+// moving them across this point.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D, int NB>
+// APPEND = true is the fused decode step: seq_lens counts a new token whose K/V row is NOT in the
+// cache yet but in k_new / v_new.  The wave whose range holds that position writes the row into
+// its page (for later steps) and patches it into its own LDS copy of the last block (for this
+// step), so the separate append launch in front of every decode step disappears.
+template <int D, int NB, bool APPEND>
 __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   using G = TileGeom<D>;
   using Z = SwzTile<D>;
@@ -114,6 +128,15 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
         qreg[s] = *reinterpret_cast<bf16x8 *>(&z);
       }
     }
+  }
+  // this step's new K/V row, one 16-byte chunk per lane (64 / CPR copies of the row per wave);
+  // requested by every wave, used by the one that owns the position
+  constexpr int CPR = D / 8;  // 16-byte chunks per row
+  u32x4 knew = {0, 0, 0, 0}, vnew = {0, 0, 0, 0};
+  if (APPEND) {
+    const size_t noff = (((size_t)seq * a.Hkv + kvh) * CPR + (lane % CPR)) * 16;
+    knew = *reinterpret_cast<const u32x4 *>(a.k_new + noff);
+    vnew = *reinterpret_cast<const u32x4 *>(a.v_new + noff);
   }
   const int L = a.seq_lens[seq];
   if (kv0 >= L) {  // nothing to attend to: an empty partial, so the combine pass needs no lengths
@@ -220,6 +243,28 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     else wait_vmcnt<0>();
     const lds_char *sb = smem + (i % NB) * SLOT;
     const int base = kv0 + 32 * i;
+    if (APPEND && kv1 == L && i == nb - 1) {
+      // The block that holds position L-1 has landed (it is the last one: nothing behind it).
+      // Its row for that position and the rows after it (redirected to it) are stale cache
+      // bytes: overwrite them in LDS with the new row, and store the row to its page.
+      const int r_new = last_row & 31;  // row of the new token inside this block
+      const int c = lane % CPR;
+#pragma unroll
+      for (int j = 0; j < 32 * CPR / 64; ++j) {
+        const int row = j * (64 / CPR) + lane / CPR;
+        if (row >= r_new) {
+          *(lds_u32x4 *)(smem + (i % NB) * SLOT + Z::template offset<false>(row, c)) = knew;
+          *(lds_u32x4 *)(smem + (i % NB) * SLOT + MBYTES + Z::template offset<true>(row, c)) = vnew;
+        }
+      }
+      if (lane < CPR && head0 % a.group == 0) {  // one writer per (sequence, KV head)
+        const int pg = __builtin_amdgcn_readlane(my_page, last_row >> 4);
+        const size_t dst = (size_t)(unsigned)pg * page_stride + (size_t)((kv0 + last_row) & 15) * ROWB + c * 16;
+        *reinterpret_cast<u32x4 *>(const_cast<char *>(kpool) + dst) = knew;
+        *reinterpret_cast<u32x4 *>(const_cast<char *>(vpool) + dst) = vnew;
+      }
+      wave_lds_fence();
+    }
 
     f32x16 sacc, sacc1;  // two accumulators halve the dependent MFMA chain a lone wave sits through
 #pragma unroll
@@ -449,11 +494,11 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
   return SP_OK;
 }
 
-template <int D, int NB>
+template <int D, int NB, bool APPEND>
 static int launch_split(const DecodeArgs &a, int batch, hipStream_t stream) {
   static bool attr_set = false;  // benign if two threads race
   constexpr int smem = NB * 2 * 32 * D * 2;
-  auto fn = decode_split_kernel<D, NB>;
+  auto fn = decode_split_kernel<D, NB, APPEND>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return fail(SP_ERR_HIP, "decode smem attribute: %s", hipGetErrorString(e));
@@ -468,23 +513,27 @@ static int launch_decode_d(DecodeArgs &a, char *out, int batch, hipStream_t stre
   long gy = (long)batch * a.n_hgroups;
   if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_decode: batch * head groups = %ld exceeds 65535", gy);
   const int ring = g_ring_override > 0 ? g_ring_override : 2;  // more resident waves beat a deeper ring (measured)
-  int rc = ring == 2 ? launch_split<D, 2>(a, batch, stream)
-         : ring == 3 ? launch_split<D, 3>(a, batch, stream)
-                     : launch_split<D, 4>(a, batch, stream);
+  int rc;
+  if (a.k_new) rc = launch_split<D, 2, true>(a, batch, stream);  // fused step: the measured-best ring only
+  else rc = ring == 2 ? launch_split<D, 2, false>(a, batch, stream)
+          : ring == 3 ? launch_split<D, 3, false>(a, batch, stream)
+                      : launch_split<D, 4, false>(a, batch, stream);
   if (rc != SP_OK) return rc;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "decode split launch: %s", hipGetErrorString(e));
   return launch_combine(a.part_o, a.part_ml, out, (long)batch * a.Hq, a.nsplit, D, stream);
 }
 
-int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
-                  const int32_t *block_table, int batch, int max_pages, int max_seq_len,
-                  int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
+int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
+                  const int32_t *seq_lens, const int32_t *block_table, int batch, int max_pages,
+                  int max_seq_len, int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
                   hipStream_t stream) {
   (void)workspace_bytes;
   DecodeArgs a;
   a.k_pages = (const char *)c.k_pages;
   a.v_pages = (const char *)c.v_pages;
+  a.k_new = (const char *)k_new;  // both NULL: the rows are in the cache already
+  a.v_new = (const char *)v_new;
   a.q = (const char *)q;
   a.seq_lens = seq_lens;
   a.block_table = block_table;

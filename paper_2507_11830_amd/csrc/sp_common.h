@@ -48,9 +48,10 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
                    hipStream_t stream);
 
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);
-int launch_decode(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
-                  const int32_t *block_table, int batch, int max_pages, int max_seq_len,
-                  int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
+// k_new / v_new non-NULL: fused decode step (the new token's rows are appended by the kernel).
+int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
+                  const int32_t *seq_lens, const int32_t *block_table, int batch, int max_pages,
+                  int max_seq_len, int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
                   hipStream_t stream);
 
 }  // namespace sp

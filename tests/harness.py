@@ -65,6 +65,23 @@ class GpuRunner:
         torch.cuda.synchronize()
         return bits_of(out)
 
+    def decode_step(self, st: W.Step):
+        """Fused append + decode of a step in which every sequence has exactly one new token."""
+        import torch
+
+        w, sp = self.w, self.sp
+        assert st.kind == "decode" and (st.new_lens == 1).all()
+        q = to_dev(st.q)
+        out = torch.empty_like(q)
+        mx = int(st.seq_lens.max())
+        need = sp.sp_attn_decode_workspace_size(w.batch, mx, w.Hq, w.d)
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda")
+        sp.sp_decode_step(self.cache, to_dev(st.k_new), to_dev(st.v_new), q, out, dev_i32(st.seq_lens), self.bt, mx,
+                          float(w.scale), self.ws)
+        torch.cuda.synchronize()
+        return bits_of(out)
+
     def cache_bits(self):
         return bits_of(self.cache.k_pages), bits_of(self.cache.v_pages)
 

@@ -149,6 +149,42 @@ def test_prefill_without_workspace_matches_with_workspace():
     assert np.abs(outs[0] - want).max() <= TOL and np.abs(outs[1] - want).max() <= TOL
 
 
+def run_fused_steps(w):
+    """Decode steps through sp_decode_step (append fused into the attention launch) against the
+    oracle's append + decode; the cache image must come out bit-identical as well."""
+    g, o = GpuRunner(w), OracleRunner(w)
+    worst = 0.0
+    for i, st in enumerate(w.steps()):
+        o.append(st)
+        if st.kind == "decode":
+            worst = max(worst, report_err(f"{w.name} fused step {i}", g.decode_step(st), o.attend(st)))
+        else:
+            g.append(st)
+            if st.kind == "prefill":
+                worst = max(worst, report_err(f"{w.name} step {i} prefill", g.attend(st), o.attend(st)))
+    gk, gv = g.cache_bits()
+    assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp), "cache image differs from the oracle's"
+    assert worst <= TOL
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 1, 128), (2, 1, 64), (32, 8, 128), (6, 2, 128), (40, 1, 64)])
+def test_fused_decode_step_small_ragged(Hq, Hkv, d):
+    """New token on every position class: first row of a page, last row, page interior, first token
+    of a sequence (length 1), block boundaries, split boundaries (lengths 1025 / 2049)."""
+    lens = np.array([1, 15, 16, 17, 32, 33, 127, 128, 129, 255, 256, 257, 1000, 1024, 1025, 2049])
+    run_fused_steps(custom_workload(f"fused-{Hq}-{Hkv}-{d}", lens, lens - 1, Hq, Hkv, d, "decode", seed=81))
+
+
+def test_fused_decode_steps_c1_and_repeated():
+    """C1's 16 consecutive decode steps on one growing sequence, every step fused: each step reads
+    the rows the previous fused steps wrote."""
+    run_fused_steps(W.c1_tiny())
+
+
+def test_fused_decode_step_c3_full():
+    run_fused_steps(W.c3_decode())
+
+
 @pytest.mark.parametrize("length", [5000, 20000])
 def test_decode_single_long_sequence_many_splits(length):
     """One long sequence: 40 resp. 157 splits per row, so the combine pass runs its four- resp.
