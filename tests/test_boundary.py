@@ -122,3 +122,14 @@ def test_tuning_keys_are_validated(built_lib):
         assert L.sp_debug_set_tuning(b"prefill_kv_splits", v) == want
     for key in (b"decode_chunk", b"decode_ring", b"prefill_split", b"prefill_kv_splits"):
         assert L.sp_debug_set_tuning(key, 0) == sp.SP_OK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU's shard only: asking bench.py for more must end with a message, before any GPU use."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
