@@ -316,6 +316,22 @@ def extra_shift_decode(sp, steps=64):
             "GBps_cache_resident": nbytes / per[1] / 1e6}
 
 
+def extra_head_exchange(sp):
+    """Local halves of the SP-mode head exchange at the 70B shape: one rank's 1024 of 8192 prefill
+    tokens, q with all 64 heads -> 8 blocks of 8 heads (pack) and back (unpack)."""
+    import torch
+
+    T, H, d, P = 1024, 64, 128, 8
+    x = torch.randn((T, H, d), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    send = torch.empty((P, T, H // P, d), device="cuda", dtype=torch.bfloat16)
+    y = torch.empty_like(x)
+    _, per = time_phases([lambda: sp.sp_ulysses_pack(x, send, P), lambda: sp.sp_ulysses_unpack(send, y)], 20, 3)
+    nbytes = 2 * x.numel() * 2
+    return {"workload": "SP-mode head exchange, local pack / unpack of [1024][64][128] bf16 over 8 ranks",
+            "us_pack": per[0] * 1e3, "us_unpack": per[1] * 1e3, "GBps_pack_read_plus_write": nbytes / per[0] / 1e6,
+            "GBps_unpack_read_plus_write": nbytes / per[1] / 1e6}
+
+
 def ceilings(sp):
     """What this machine delivers for the two bounding resources: a register-resident bf16 MFMA loop
     and a 16 B/lane streaming read of 2 GiB (both kernels live in the library)."""
@@ -431,7 +447,7 @@ def main():
         res["roofline"]["frac_of_measured_mfma_loop"] = tflops / ceil["mfma_loop_TFLOPs"]
         res["roofline_decode"]["frac_of_measured_stream_read"] = gbps / ceil["stream_read_GBps"]
         res["other_workloads"] = [extra_long_prefill(sp), extra_big_decode(sp), extra_chunked_prefill(sp),
-                                  extra_shift_decode(sp)]
+                                  extra_shift_decode(sp), extra_head_exchange(sp)]
         for o in res["other_workloads"]:
             if "TFLOPs" in o:
                 o["frac_of_measured_mfma_loop"] = o["TFLOPs"] / ceil["mfma_loop_TFLOPs"]

@@ -145,6 +145,23 @@ size_t sp_attn_decode_workspace_size(int32_t batch, int32_t max_seq_len, int32_t
                                      int32_t head_dim);
 
 /*
+ * sp_ulysses_pack / sp_ulysses_unpack — the local halves of the sequence-parallel head exchange
+ * (the steps either side of the attention path in SP mode; the all-to-all itself is not part of
+ * this library).  A rank holds `tokens` tokens with all `num_heads` heads; `world` ranks.
+ *   pack    x     bf16 [tokens][num_heads][head_dim]
+ *           send  bf16 [world][tokens][num_heads / world][head_dim]; block j holds head slice j,
+ *                 contiguous, ready to be sent to rank j
+ *   unpack  recv  bf16 [world][tokens][num_heads / world][head_dim]; block j came from rank j
+ *           y     bf16 [tokens][num_heads][head_dim]
+ * Pure bit copies (unpack inverts pack).  num_heads % world != 0 -> SP_ERR_BAD_SHAPE; head_dim
+ * must be a multiple of 8; in-place use is refused; tokens == 0 is a no-op.
+ */
+int sp_ulysses_pack(const void *x, void *send, int32_t tokens, int32_t num_heads,
+                    int32_t head_dim, int32_t world, void *stream);
+int sp_ulysses_unpack(const void *recv, void *y, int32_t tokens, int32_t num_heads,
+                      int32_t head_dim, int32_t world, void *stream);
+
+/*
  * sp_debug_validate_metadata — SYNCHRONOUS test helper: copies the int32 arrays to the host
  * and checks 0 <= page < num_pages for every page a sequence uses and
  * ceil(seq_lens[s] / 16) <= max_pages_per_seq.  Returns SP_OK or SP_ERR_BAD_SHAPE.

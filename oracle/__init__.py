@@ -180,3 +180,24 @@ def attn_row_subset(k_pages, v_pages, bt_row, p, mask, q_row, g, scale):
         ctypes.c_double(float(scale)), _p(out), _p(lse),
     )
     return out, float(lse[0])
+
+
+def ulysses_pack(x, P: int) -> np.ndarray:
+    """x: uint16 [T_loc, H, d] (all heads of this rank's tokens) -> send buffer [P, T_loc, H/P, d]
+    (block j goes to rank j).  Local half of the pre-attention exchange of the SP mode."""
+    x = _u16(x)
+    T, H, d = x.shape
+    assert H % P == 0
+    send = np.empty((P, T, H // P, d), dtype=np.uint16)
+    _load().oracle_ulysses_pack(_p(x), _p(send), T, H, d, P)
+    return send
+
+
+def ulysses_unpack(recv) -> np.ndarray:
+    """recv: uint16 [P, T_loc, H/P, d] (block j came from rank j) -> [T_loc, H, d].  Local half of
+    the post-attention exchange."""
+    recv = _u16(recv)
+    P, T, hp, d = recv.shape
+    y = np.empty((T, P * hp, d), dtype=np.uint16)
+    _load().oracle_ulysses_unpack(_p(recv), _p(y), T, P * hp, d, P)
+    return y

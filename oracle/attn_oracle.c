@@ -254,3 +254,33 @@ void oracle_attn_prefill_rows(const uint16_t *k_pages, const uint16_t *v_pages, 
                           out + (size_t)r * d, NULL, NULL);
   }
 }
+
+/*
+ * The local halves of the sequence-parallel head exchange (paper section on Arctic Sequence
+ * Parallelism: the sequence is split across the P GPUs, and Figure 2: in the SP mode every GPU
+ * attends with its own subset of the heads over all tokens).  Before attention a GPU holds its
+ * T_loc tokens with ALL H heads and must hand head slice j to GPU j; after attention it gets
+ * its tokens' outputs back one head slice per peer.  With tokens distributed in contiguous
+ * slices in rank order, the exchange itself is a plain all-to-all of equal blocks and only
+ * these two permutations remain local (bit copies, written out index by index):
+ *
+ *   pack:    send[j][t][h'][c] = x[t][j * (H/P) + h'][c]          x: [T_loc][H][d]
+ *   unpack:  y[t][j * (H/P) + h'][c] = recv[j][t][h'][c]          recv: [P][T_loc][H/P][d]
+ */
+void oracle_ulysses_pack(const uint16_t *x, uint16_t *send, int T_loc, int H, int d, int P) {
+  int hp = H / P;
+  for (int j = 0; j < P; ++j)
+    for (int t = 0; t < T_loc; ++t)
+      for (int h = 0; h < hp; ++h)
+        for (int c = 0; c < d; ++c)
+          send[(((size_t)j * T_loc + t) * hp + h) * d + c] = x[((size_t)t * H + (size_t)j * hp + h) * d + c];
+}
+
+void oracle_ulysses_unpack(const uint16_t *recv, uint16_t *y, int T_loc, int H, int d, int P) {
+  int hp = H / P;
+  for (int j = 0; j < P; ++j)
+    for (int t = 0; t < T_loc; ++t)
+      for (int h = 0; h < hp; ++h)
+        for (int c = 0; c < d; ++c)
+          y[((size_t)t * H + (size_t)j * hp + h) * d + c] = recv[(((size_t)j * T_loc + t) * hp + h) * d + c];
+}

@@ -23,7 +23,8 @@ SP_ERR_WORKSPACE = -4
 SP_ERR_HIP = -5
 
 EXPORTS = (
-    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_decode_step", "sp_attn_prefill_workspace_size",
+    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_decode_step", "sp_ulysses_pack", "sp_ulysses_unpack",
+    "sp_attn_prefill_workspace_size",
     "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_set_tuning",
     "sp_debug_ceiling_mfma", "sp_debug_ceiling_stream", "sp_status_string",
     "sp_last_error", "sp_version",
@@ -66,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.sp_attn_decode.restype = ctypes.c_int
         L.sp_decode_step.argtypes = [cd, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, sz, vp]
         L.sp_decode_step.restype = ctypes.c_int
+        L.sp_ulysses_pack.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        L.sp_ulysses_pack.restype = ctypes.c_int
+        L.sp_ulysses_unpack.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+        L.sp_ulysses_unpack.restype = ctypes.c_int
         L.sp_attn_prefill_workspace_size.argtypes = [i32, i32, i32, i32]
         L.sp_attn_prefill_workspace_size.restype = sz
         L.sp_attn_decode_workspace_size.argtypes = [i32, i32, i32, i32]
@@ -219,3 +224,15 @@ def sp_debug_ceiling_stream(buf, sink, stream=None) -> int:
     _check(lib().sp_debug_ceiling_stream(_ptr(buf), nbytes, _ptr(sink), sink.numel() * sink.element_size(),
                                          _stream(stream)))
     return nbytes
+
+
+def sp_ulysses_pack(x, send, world: int, stream=None) -> None:
+    """x: bf16 [T_loc, H, d] -> send: bf16 [world, T_loc, H/world, d] (block j = head slice j)."""
+    t, h, d = x.shape
+    _check(lib().sp_ulysses_pack(_ptr(x), _ptr(send), t, h, d, int(world), _stream(stream)))
+
+
+def sp_ulysses_unpack(recv, y, stream=None) -> None:
+    """recv: bf16 [world, T_loc, H/world, d] -> y: bf16 [T_loc, H, d]."""
+    world, t, hp, d = recv.shape
+    _check(lib().sp_ulysses_unpack(_ptr(recv), _ptr(y), t, hp * world, d, world, _stream(stream)))

@@ -126,6 +126,30 @@ int sp_decode_step(const sp_cache_desc *cache, const void *k_new, const void *v_
                        max_pages_per_seq, max_seq_len, num_q_heads, scale, workspace, workspace_bytes, stream);
 }
 
+static int ulysses_common(bool pack, const void *src, void *dst, int32_t tokens, int32_t num_heads,
+                          int32_t head_dim, int32_t world, void *stream) {
+  if (tokens < 0 || num_heads <= 0 || world <= 0)
+    return fail(SP_ERR_BAD_SHAPE, "tokens=%d num_heads=%d world=%d", tokens, num_heads, world);
+  if (num_heads % world != 0)
+    return fail(SP_ERR_BAD_SHAPE, "num_heads=%d is not a multiple of world=%d", num_heads, world);
+  if (head_dim <= 0 || head_dim % 8 != 0)
+    return fail(SP_ERR_UNSUPPORTED, "head_dim=%d must be a positive multiple of 8", head_dim);
+  if (tokens == 0) return SP_OK;
+  if (!src || !dst) return fail(SP_ERR_NULL, "ulysses permute: NULL buffer");
+  if (src == dst) return fail(SP_ERR_UNSUPPORTED, "ulysses permute: in-place use is not supported");
+  return launch_ulysses(pack, src, dst, tokens, num_heads, head_dim, world, (hipStream_t)stream);
+}
+
+int sp_ulysses_pack(const void *x, void *send, int32_t tokens, int32_t num_heads, int32_t head_dim,
+                    int32_t world, void *stream) {
+  return ulysses_common(true, x, send, tokens, num_heads, head_dim, world, stream);
+}
+
+int sp_ulysses_unpack(const void *recv, void *y, int32_t tokens, int32_t num_heads, int32_t head_dim,
+                      int32_t world, void *stream) {
+  return ulysses_common(false, recv, y, tokens, num_heads, head_dim, world, stream);
+}
+
 size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens, int32_t num_q_heads,
                                       int32_t head_dim) {
   (void)batch;

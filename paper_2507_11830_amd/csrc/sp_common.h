@@ -35,6 +35,9 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
                    void *workspace, size_t workspace_bytes, hipStream_t stream);
 size_t prefill_workspace_bytes(int total_q_tokens, int num_q_heads, int head_dim);
 
+// [T_loc][H][d] <-> [P][T_loc][H/P][d] (pack = to the blocked side), bf16 elements.
+int launch_ulysses(bool pack, const void *src, void *dst, int T_loc, int H, int d, int P, hipStream_t stream);
+
 // Tuning hooks behind sp_debug_set_tuning (0 restores the built-in heuristic).
 void set_decode_chunk(int chunk);
 void set_decode_ring(int slots);   // LDS ring depth of the decode split kernel: 0 heuristic, 2..4

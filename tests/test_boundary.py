@@ -100,6 +100,13 @@ def test_argument_validation_needs_no_gpu(built_lib):
     assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 4, 64, 1000, 8, 0.1, one, 16, None) == sp.SP_ERR_WORKSPACE
     assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 4, 64, 1000, 8, 0.1, None, 0, None) == sp.SP_ERR_WORKSPACE
     assert b"workspace" in L.sp_last_error()
+    # head exchange permutations
+    assert L.sp_ulysses_pack(one, one, 4, 8, 128, 3, None) == sp.SP_ERR_BAD_SHAPE       # 8 heads over 3 ranks
+    assert L.sp_ulysses_pack(one, one, 4, 8, 100, 2, None) == sp.SP_ERR_UNSUPPORTED     # head_dim % 8
+    assert L.sp_ulysses_pack(one, one, 4, 8, 128, 2, None) == sp.SP_ERR_UNSUPPORTED     # in place
+    assert L.sp_ulysses_unpack(None, one, 4, 8, 128, 2, None) == sp.SP_ERR_NULL
+    assert L.sp_ulysses_unpack(None, None, 0, 8, 128, 2, None) == sp.SP_OK
+    assert L.sp_decode_step(ctypes.byref(d), None, one, one, one, one, one, 4, 64, 1000, 8, 0.1, one, 1 << 30, None) == sp.SP_ERR_NULL
     # empty batches are legal no-ops
     assert L.sp_attn_prefill(ctypes.byref(d), one, one, one, one, one, 0, 1, 0, 0, 0, 8, 0.1, 1, None, 0, None) == sp.SP_OK
     assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 0, 1, 0, 8, 0.1, None, 0, None) == sp.SP_OK

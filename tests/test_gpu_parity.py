@@ -338,3 +338,31 @@ def test_c5_long_context_shift_same_cache():
 
 def test_c5c_8b_shape_decode_batch():
     run_full_compare(W.c5c_decode_8b(batch=32), check_cache=False)
+
+
+# ------------------------------------------------------------------ head exchange permutations
+@pytest.mark.parametrize("T,H,d,P", [(1000, 64, 128, 8), (777, 8, 128, 8), (513, 8, 64, 2), (1, 6, 128, 3), (300, 32, 128, 1)])
+def test_ulysses_pack_unpack_bit_exact(T, H, d, P):
+    """The local halves of the SP-mode head exchange: bit-exact against the oracle's index-by-index
+    permutation, canaries around the destination untouched, unpack(pack(x)) == x on the GPU."""
+    import oracle
+    import torch
+    import paper_2507_11830_amd as sp
+
+    rng = np.random.default_rng(90 + T)
+    x = rng.integers(0, 65536, size=(T, H, d)).astype(np.uint16)
+    want = oracle.ulysses_pack(x, P)
+    xd = to_dev(x)
+    guard = 64
+    buf = torch.full((P * T * (H // P) * d + 2 * guard,), W.CANARY, dtype=torch.int16, device="cuda")
+    send = buf[guard:-guard].view(torch.bfloat16).view(P, T, H // P, d)
+    sp.sp_ulysses_pack(xd, send, P)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(send), want)
+    edges = buf.cpu().numpy().view(np.uint16)
+    assert (edges[:guard] == 0x7FC0).all() and (edges[-guard:] == 0x7FC0).all()
+    y = torch.empty_like(xd)
+    sp.sp_ulysses_unpack(send, y)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(y), x)
+    assert np.array_equal(bits_of(y), oracle.ulysses_unpack(want))

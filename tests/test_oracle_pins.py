@@ -385,3 +385,44 @@ def test_two_key_row_is_a_sigmoid(oracle):
     assert abs(w[1] - sig) <= 1e-15 and abs(w[0] - (1 - sig)) <= 1e-15
     assert abs(o[0] - (2.0 * (1 - sig) - 3.0 * sig)) <= 1e-14
     assert abs(lse - (0.75 * 1.5 * 0.5 + math.log1p(math.exp(x)))) <= 1e-14
+
+
+# ------------------------------------------------------------------ head exchange permutations
+def _tagged(T, H, d):
+    """Element (t, h, c) carries its own coordinates: t in the high bits, h and c below."""
+    t, h, c = np.meshgrid(np.arange(T), np.arange(H), np.arange(d), indexing="ij")
+    return (t * 1024 + h * 32 + c).astype(np.uint16)
+
+
+@pytest.mark.parametrize("T,H,d,P", [(5, 8, 16, 2), (3, 8, 8, 8), (7, 6, 24, 3), (4, 4, 8, 1)])
+def test_p14_ulysses_pack_is_the_head_slice_view(oracle, T, H, d, P):
+    """Pack against the library transpose (block j = heads [j*H/P, (j+1)*H/P) of every token),
+    against the coordinates each element carries, and unpack as its inverse."""
+    x = _tagged(T, H, d)
+    send = oracle.ulysses_pack(x, P)
+    assert send.shape == (P, T, H // P, d)
+    assert np.array_equal(send, x.reshape(T, P, H // P, d).transpose(1, 0, 2, 3))
+    for j in range(P):
+        for hl in range(H // P):
+            blk = send[j, :, hl, :]
+            assert ((blk >> 10) == np.arange(T)[:, None]).all()          # token stays in place
+            assert (((blk >> 5) & 31) == j * (H // P) + hl).all()          # head slice j, local head hl
+            assert ((blk & 31) == np.arange(d)[None, :]).all()            # channels untouched
+    assert np.array_equal(oracle.ulysses_unpack(send), x)
+
+
+def test_p14_ulysses_exchange_end_to_end(oracle):
+    """P simulated ranks: pack on every rank, exchange block j of rank i with block i of rank j,
+    and the received buffer of rank j read as [T][H/P][d] is the head slice j of the full
+    sequence, tokens in rank order; unpack on the way back restores every rank's rows."""
+    rng = np.random.default_rng(14)
+    P, T_loc, H, d = 4, 6, 8, 16
+    full = rng.integers(0, 65536, size=(P * T_loc, H, d)).astype(np.uint16)
+    sends = [oracle.ulysses_pack(full[r * T_loc:(r + 1) * T_loc], P) for r in range(P)]
+    for j in range(P):
+        recv = np.stack([sends[i][j] for i in range(P)])                   # the all-to-all
+        assert np.array_equal(recv.reshape(P * T_loc, H // P, d), full[:, j * (H // P):(j + 1) * (H // P), :])
+    # the way back: rank j returns to rank i the block of rank i's tokens
+    for i in range(P):
+        back = np.stack([full[i * T_loc:(i + 1) * T_loc, j * (H // P):(j + 1) * (H // P), :] for j in range(P)])
+        assert np.array_equal(oracle.ulysses_unpack(back), full[i * T_loc:(i + 1) * T_loc])
