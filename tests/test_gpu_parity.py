@@ -340,6 +340,17 @@ def test_c5c_8b_shape_decode_batch():
     run_full_compare(W.c5c_decode_8b(batch=32), check_cache=False)
 
 
+def test_very_long_context_chunk_and_decode():
+    """A 100 000-token cached prefix (1.6 k key tiles, 6 k pages): a 48-token chunk prefilled on it
+    (key range cut into the maximum number of pieces) and a fused decode step after it (782 splits,
+    eight-wave combine), both against the oracle."""
+    lens = np.array([100048])
+    w = custom_workload("long-100k", lens, lens - 48, 8, 1, 128, "prefill", seed=91)
+    run_full_compare(w)
+    lens = np.array([100001, 70000])
+    run_fused_steps(custom_workload("long-100k-decode", lens, lens - 1, 8, 1, 128, "decode", seed=92))
+
+
 # ------------------------------------------------------------------ head exchange permutations
 @pytest.mark.parametrize("T,H,d,P", [(1000, 64, 128, 8), (777, 8, 128, 8), (513, 8, 64, 2), (1, 6, 128, 3), (300, 32, 128, 1)])
 def test_ulysses_pack_unpack_bit_exact(T, H, d, P):
