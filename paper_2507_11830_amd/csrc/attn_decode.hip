@@ -213,16 +213,6 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     for (int db = 0; db < G::kDBlocks; ++db)
       vofs[db] = MBYTES + Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) + 8 * (n & 1);
   }
-  auto read_vt = [&](const lds_char *p) -> bf16x8 {  // key rows r..r+3 and r+8..r+11 of one 32-channel block
-    union {
-      struct { s16x4 a, b; } s;
-      bf16x8 v;
-    } u;
-    u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
-    u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * ROWB));
-    return u.v;
-  };
-
   f32x16 o[G::kDBlocks];
 #pragma unroll
   for (int db = 0; db < G::kDBlocks; ++db)
@@ -316,7 +306,7 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int db = 0; db < G::kDBlocks; ++db) {
-        bf16x8 vop = read_vt(sb + vofs[db] + 16 * ks * ROWB);
+        bf16x8 vop = lds_read_vt(sb + vofs[db] + 16 * ks * ROWB, ROWB);
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
       }
     if (L <= 64) {  // very short sequences: weights as hi + lo, so bf16 rounding of P stays out of the tolerance
@@ -325,7 +315,7 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int db = 0; db < G::kDBlocks; ++db) {
-          bf16x8 vop = read_vt(sb + vofs[db] + 16 * ks * ROWB);
+          bf16x8 vop = lds_read_vt(sb + vofs[db] + 16 * ks * ROWB, ROWB);
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[ks], o[db], 0, 0, 0);
         }
     }

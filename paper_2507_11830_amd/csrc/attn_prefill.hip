@@ -278,14 +278,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   auto load_op = [&](int i) -> bf16x8 {
     if (i < NPV) {
       int db = i % G::kDBlocks, ks = (i / G::kDBlocks) & 1, b = i / (2 * G::kDBlocks);
-      const lds_char *p = smem + vcur[db] + (32 * b + 16 * ks) * ROWB;
-      union {
-        struct { s16x4 a, b; } s;
-        bf16x8 v;
-      } u;
-      u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
-      u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * ROWB));
-      return u.v;
+      return lds_read_vt(smem + vcur[db] + (32 * b + 16 * ks) * ROWB, ROWB);
     }
     int j = i - NPV;
     int s = j % G::kDSteps, b = j / G::kDSteps;
@@ -406,11 +399,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   if (grp == 0) {
 #pragma unroll
     for (int g = 0; g < NSTREAM; ++g) {
-      TileLoad k0 = dma_prep(false, g, stream_tile(g, 0), page_of(stream_tile(g, 0)), 0);
+      const int gt0 = stream_tile(g, 0);
+      const int pg0 = page_of(gt0);
+      TileLoad k0 = dma_prep(false, g, gt0, pg0, 0);
 #pragma unroll
       for (int j = 0; j < NIW; ++j) dma_emit(false, k0, j);
       pg_k[g] = page_of(stream_tile(g, 1));
-      pg_v[g] = page_of(stream_tile(g, 0));
+      pg_v[g] = pg0;
     }
   }
   wait_loads();

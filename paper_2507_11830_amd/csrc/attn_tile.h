@@ -22,9 +22,6 @@ namespace sp {
 
 template <int D>
 struct TileGeom {
-  static constexpr int kChunksPerRow = D / 8;   // 16-byte chunks in one K or V row
-  static constexpr int kKStride = D * 2 + 16;   // bytes; +16 spreads 16 consecutive rows over all banks
-  static constexpr int kVStride = D * 2 + 64;   // bytes; +64 makes 4 consecutive rows x 64 B bank-disjoint
   static constexpr int kDSteps = D / 16;        // MFMA k-steps of the QK^T contraction
   static constexpr int kDBlocks = D / 32;       // 32-row blocks of O^T
 };
@@ -36,29 +33,22 @@ typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 typedef __attribute__((address_space(3))) float lds_float;
 
-__device__ __forceinline__ bf16x8 lds_read_k_operand(const lds_char *kbuf, int kstride, int row, int dchunk) {
-  return *(const lds_bf16x8 *)(kbuf + row * kstride + dchunk * 16);
-}
-
-// V^T operand for one (32-row d-block, 16-key step): two transposing 8-byte reads.
-// `vrow0` is the first of the 4 consecutive key rows this wave half supplies (the second
-// group of 4 sits 8 rows further), `dcol0` the first d column of the 32-wide block.
-__device__ __forceinline__ bf16x8 lds_read_vt_operand(const lds_char *vbuf, int vstride, int vrow0,
-                                                      int dcol0, int lane) {
-  int n = lane & 15, dg = (lane >> 4) & 1;
-  const lds_char *p = vbuf + (vrow0 + (n >> 2)) * vstride + (dcol0 + 16 * dg + 4 * (n & 3)) * 2;
-  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * vstride));
+// V^T operand for one (32-channel block, 16-key step): two transposing 8-byte reads.  `p` is
+// this lane's address for the first of its 4 consecutive key rows (lane n of a 16-lane group
+// supplies row n / 4 and 8-byte piece n % 4 of a 32-byte run of channels); the second group of
+// 4 rows sits 8 rows (8 * rowbytes) further.  Row offsets that are multiples of 8 rows leave the
+// swizzle of SwzTile unchanged, so callers add them to a precomputed lane address.
+__device__ __forceinline__ bf16x8 lds_read_vt(const lds_char *p, int rowbytes) {
   union {
     struct { s16x4 a, b; } s;
     bf16x8 v;
   } u;
-  u.s.a = lo;
-  u.s.b = hi;
+  u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+  u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * rowbytes));
   return u.v;
 }
 
-// Swizzled, unpadded tile layout (prefill kernel).  Tiles are brought in with direct
+// Swizzled, unpadded tile layout.  Tiles are brought in with direct
 // global -> LDS loads, which place the 64 lanes' 16-byte chunks back to back; padding between
 // rows is therefore impossible, but every lane may fetch ANY global chunk, so the bank spread
 // comes from a permutation instead: a tile is a sequence of 256-byte lines (one row at
