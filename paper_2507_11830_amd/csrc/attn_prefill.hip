@@ -395,17 +395,25 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       for (int ks = 0; ks < 2; ++ks) pop[b][ks] = pack8(sacc[b], 8 * ks);
   };
 
-  // prologue: K of every stream's first tile must be in LDS before anything is multiplied
+  // prologue: K of every stream's first tile must be in LDS before anything is multiplied.  V of
+  // that tile and K of the second one are requested in the same round trip (their slots are
+  // free), so the first period has no load to wait for: a memory latency per workgroup that
+  // small grids cannot hide behind other work.
   if (grp == 0) {
 #pragma unroll
     for (int g = 0; g < NSTREAM; ++g) {
-      const int gt0 = stream_tile(g, 0);
-      const int pg0 = page_of(gt0);
-      TileLoad k0 = dma_prep(false, g, gt0, pg0, 0);
+      const int gt0 = stream_tile(g, 0), gt1 = stream_tile(g, 1);
+      const int pg0 = page_of(gt0), pg1 = page_of(gt1);
+      TileLoad k0 = dma_prep(false, g, gt0, pg0, 0), v0 = dma_prep(true, g, gt0, pg0, 0);
+      TileLoad k1 = dma_prep(false, g, gt1, pg1, 1);
 #pragma unroll
       for (int j = 0; j < NIW; ++j) dma_emit(false, k0, j);
-      pg_k[g] = page_of(stream_tile(g, 1));
-      pg_v[g] = pg0;
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) dma_emit(true, v0, j);
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) dma_emit(false, k1, j);
+      pg_k[g] = page_of(stream_tile(g, 2));
+      pg_v[g] = pg1;
     }
   }
   wait_loads();
@@ -417,16 +425,14 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // One wave of each group sits on every SIMD, so the matrix pipe and the VALU are both busy
   // through the whole period, and since nothing forces the phase boundary to line up, a short
   // softmax simply lets the next MFMA phase start early.
-  // Buffer hand-off: K(t+1) and V(t) are requested in the first group's MFMA phase of period t
-  // into the slots last read in period t-1, have landed before the barrier that ends period t,
-  // and are first read in period t+1.
+  // Buffer hand-off: from period 1 on, K(t+1) and V(t) are requested in the first group's MFMA
+  // phase of period t into the slots last read in period t-1, have landed before the barrier
+  // that ends period t, and are first read in period t+1.
   if (grp == 0) {  // always has Tl == P >= 1
-    issue_prep(0);
     __builtin_amdgcn_s_setprio(3);
-    qk(true_type{});
+    qk(false_type{});  // the loads of period 0 went out in the prologue
     __builtin_amdgcn_s_setprio(0);
     softmax(0);
-    wait_loads();
     __syncthreads();
     if (precise0) pv_residual0();  // V(0) became visible at the barrier; sacc still holds P(0)
     for (int t = 1; t < Tl; ++t) {

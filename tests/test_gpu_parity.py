@@ -340,6 +340,30 @@ def test_c5c_8b_shape_decode_batch():
     run_full_compare(W.c5c_decode_8b(batch=32), check_cache=False)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_against_oracle(seed):
+    """Seeded random batches (head configuration, head_dim, lengths, cached prefixes, empty
+    sequences) through prefill, separate decode and the fused decode step, launch shapes left to
+    the library's own heuristics."""
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 9))
+    hi = int(rng.choice([40, 300, 1500, 5000]))
+    total = rng.integers(1, hi + 1, size=B)
+    total[rng.random(B) < 0.15] = 0
+    if total.max() == 0:
+        total[0] = 7
+    ctx = (total * rng.random(B) * (rng.random(B) < 0.7)).astype(np.int64)
+    ctx = np.minimum(ctx, np.maximum(total - 1, 0))
+    print(f"[shape] seed {seed}: Hq {Hkv * G} Hkv {Hkv} d {d} total {total.tolist()} ctx {ctx.tolist()}", flush=True)
+    run_full_compare(custom_workload(f"rand-p-{seed}", total, ctx, Hkv * G, Hkv, d, "prefill", seed=2000 + seed))
+    dec = np.where(total > 0, total, 1)
+    run_full_compare(custom_workload(f"rand-d-{seed}", dec, dec - 1, Hkv * G, Hkv, d, "decode", seed=3000 + seed))
+    run_fused_steps(custom_workload(f"rand-f-{seed}", dec, dec - 1, Hkv * G, Hkv, d, "decode", seed=4000 + seed))
+
+
 def test_very_long_context_chunk_and_decode():
     """A 100 000-token cached prefix (1.6 k key tiles, 6 k pages): a 48-token chunk prefilled on it
     (key range cut into the maximum number of pieces) and a fused decode step after it (782 splits,
