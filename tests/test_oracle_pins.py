@@ -426,3 +426,25 @@ def test_p14_ulysses_exchange_end_to_end(oracle):
     for i in range(P):
         back = np.stack([full[i * T_loc:(i + 1) * T_loc, j * (H // P):(j + 1) * (H // P), :] for j in range(P)])
         assert np.array_equal(oracle.ulysses_unpack(back), full[i * T_loc:(i + 1) * T_loc])
+
+
+def test_golden_file_still_matches_the_oracle(oracle):
+    """tests/golden/c1_oracle_outputs.txt (written by tests/golden/make_golden.py from the oracle
+    alone) is a change detector: an edit to the oracle's arithmetic or to the seeded inputs must
+    show up here and be justified.  Probe values to 1e-13, cache image by hash."""
+    import importlib.util
+    import os
+
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    now = mg.render().splitlines()
+    stored = open(os.path.join(here, "c1_oracle_outputs.txt")).read().splitlines()
+    assert len(now) == len(stored)
+    assert now[1] == stored[1], "cache image changed"
+    for a, b in zip(now[2:], stored[2:]):
+        fa, fb = a.split(), b.split()
+        assert fa[:4] == fb[:4]
+        pa, pb = [float(x) for x in fa[5:8]], [float(x) for x in fb[5:8]]
+        assert np.allclose(pa, pb, rtol=0, atol=1e-13), (a, b)
