@@ -404,23 +404,15 @@ __global__ __launch_bounds__(64 * W) void combine_kernel(const float *__restrict
         }
         k = SPEC;
       }
-      for (; k + 8 <= cnt; k += 8) {  // eight independent loads in flight per lane
-        f32x2 v[8];
+      for (; k < cnt; k += 16) {  // sixteen independent loads in flight per lane; the last batch is padded
+        f32x2 v[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x2 *>(po + (long)(base + k + u) * D);
+        for (int u = 0; u < 16; ++u) v[u] = *reinterpret_cast<const f32x2 *>(po + (long)(base + min(k + u, cnt - 1)) * D);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          float fu = lane_bcast(f, k + u);
+        for (int u = 0; u < 16; ++u) {
+          float fu = k + u < cnt ? lane_bcast(f, min(k + u, 63)) : 0.f;
           a0 += fu != 0.f ? fu * v[u][0] : 0.f;
           a1 += fu != 0.f ? fu * v[u][1] : 0.f;
-        }
-      }
-      for (; k < cnt; ++k) {
-        float f0 = lane_bcast(f, k);
-        if (f0 != 0.f) {  // wave-uniform
-          f32x2 v0 = *reinterpret_cast<const f32x2 *>(po + (long)(base + k) * D);
-          a0 += f0 * v0[0];
-          a1 += f0 * v0[1];
         }
       }
     }
