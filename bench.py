@@ -339,19 +339,22 @@ def ceilings(sp):
 
     sink = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
     iters = 20000
-    fl = {}
+    out = {}
+    for name, rnd in (("mfma_loop", False), ("mfma_loop_random_operands", True)):
+        fl = {}
 
-    def mf():
-        fl["f"] = sp.sp_debug_ceiling_mfma(iters, sink)
+        def mf():
+            fl["f"] = sp.sp_debug_ceiling_mfma(iters, sink, random_operands=rnd)
 
-    _, per = time_phases([mf], 5, 2)
-    clk = sink[:16].view(torch.int64).cpu().numpy()
-    mhz = float(clk[0]) / (float(clk[1]) / 100e6) / 1e6 if clk[1] > 0 else None
+        _, per = time_phases([mf], 5, 2)
+        clk = sink[:16].view(torch.int64).cpu().numpy()
+        out[name + "_TFLOPs"] = fl["f"] / per[0] / 1e9
+        out[name + "_shader_clock_MHz"] = float(clk[0]) / (float(clk[1]) / 100e6) / 1e6 if clk[1] > 0 else None
     buf = torch.empty(1 << 31, dtype=torch.uint8, device="cuda")
     buf.fill_(1)
     _, per2 = time_phases([lambda: sp.sp_debug_ceiling_stream(buf, sink)], 5, 2)
-    return {"mfma_loop_TFLOPs": fl["f"] / per[0] / 1e9, "mfma_loop_shader_clock_MHz": mhz,
-            "stream_read_GBps": float(buf.numel()) / per2[0] / 1e6}
+    out["stream_read_GBps"] = float(buf.numel()) / per2[0] / 1e6
+    return out
 
 
 def main():
@@ -445,12 +448,14 @@ def main():
         ceil = ceilings(sp)
         res["ceilings"] = ceil
         res["roofline"]["frac_of_measured_mfma_loop"] = tflops / ceil["mfma_loop_TFLOPs"]
+        res["roofline"]["frac_of_measured_mfma_loop_random_operands"] = tflops / ceil["mfma_loop_random_operands_TFLOPs"]
         res["roofline_decode"]["frac_of_measured_stream_read"] = gbps / ceil["stream_read_GBps"]
         res["other_workloads"] = [extra_long_prefill(sp), extra_big_decode(sp), extra_chunked_prefill(sp),
                                   extra_shift_decode(sp), extra_head_exchange(sp)]
         for o in res["other_workloads"]:
             if "TFLOPs" in o:
                 o["frac_of_measured_mfma_loop"] = o["TFLOPs"] / ceil["mfma_loop_TFLOPs"]
+                o["frac_of_measured_mfma_loop_random_operands"] = o["TFLOPs"] / ceil["mfma_loop_random_operands_TFLOPs"]
             if "GBps" in o:
                 o["frac_of_measured_stream_read"] = o["GBps"] / ceil["stream_read_GBps"]
     if not args.no_cpu_baseline:

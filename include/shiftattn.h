@@ -193,7 +193,10 @@ int sp_debug_set_tuning(const char *key, int32_t value);
  * the two reference kernels a benchmark times to see what THIS chip delivers for the resources
  * the attention kernels are bound by (the published peaks assume the full boost clock).
  *   mfma    a register-resident bf16 32x32x16 MFMA loop on every CU: 8 waves per CU, `iters`
- *           rounds of four MFMAs each.  *host_flops (host pointer) receives the number of flops
+ *           (even) rounds of four MFMAs each.  random_operands == 0 multiplies the same two
+ *           operand registers over and over; != 0 cycles through eight A and eight B registers
+ *           of pseudo-random values, as a kernel working on real data does (more power, hence
+ *           a lower sustained clock).  *host_flops (host pointer) receives the number of flops
  *           the launch performs.  `sink` is device scratch of at least 16 + 4 * CUs bytes;
  *           after the launch its first two uint64 hold the shader-clock cycles and the ticks of
  *           the constant 100 MHz counter that workgroup 0 spent in the loop (their ratio is the
@@ -202,8 +205,8 @@ int sp_debug_set_tuning(const char *key, int32_t value);
  *           nontemporal; `sink` is device scratch of at least 32 * CUs bytes.
  * Both only enqueue on `stream`; the caller times them.
  */
-int sp_debug_ceiling_mfma(int32_t iters, double *host_flops, void *sink, size_t sink_bytes,
-                          void *stream);
+int sp_debug_ceiling_mfma(int32_t iters, int32_t random_operands, double *host_flops, void *sink,
+                          size_t sink_bytes, void *stream);
 int sp_debug_ceiling_stream(const void *buf, size_t bytes, void *sink, size_t sink_bytes,
                             void *stream);
 

@@ -79,7 +79,7 @@ def lib() -> ctypes.CDLL:
         L.sp_debug_validate_metadata.restype = ctypes.c_int
         L.sp_debug_set_tuning.argtypes = [ctypes.c_char_p, i32]
         L.sp_debug_set_tuning.restype = ctypes.c_int
-        L.sp_debug_ceiling_mfma.argtypes = [i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
+        L.sp_debug_ceiling_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
         L.sp_debug_ceiling_mfma.restype = ctypes.c_int
         L.sp_debug_ceiling_stream.argtypes = [vp, sz, vp, sz, vp]
         L.sp_debug_ceiling_stream.restype = ctypes.c_int
@@ -210,10 +210,10 @@ def sp_debug_set_tuning(key: str, value: int) -> None:
     _check(lib().sp_debug_set_tuning(key.encode(), int(value)))
 
 
-def sp_debug_ceiling_mfma(iters: int, sink, stream=None) -> float:
+def sp_debug_ceiling_mfma(iters: int, sink, random_operands: bool = False, stream=None) -> float:
     """Enqueues the MFMA-only reference loop; returns the flops it performs.  `sink`: cuda uint8 tensor."""
     flops = ctypes.c_double(0.0)
-    _check(lib().sp_debug_ceiling_mfma(int(iters), ctypes.byref(flops), _ptr(sink),
+    _check(lib().sp_debug_ceiling_mfma(int(iters), int(bool(random_operands)), ctypes.byref(flops), _ptr(sink),
                                        sink.numel() * sink.element_size(), _stream(stream)))
     return flops.value
 

@@ -6,26 +6,43 @@
 
 namespace sp {
 
-// 8 waves per workgroup, each with four independent 32x32x16 accumulators.
+// 8 waves per workgroup, each with four independent 32x32x16 accumulators.  RANDOM = false
+// multiplies the same two operand registers over and over (what a peak-rate loop usually does);
+// RANDOM = true cycles through eight A and eight B registers of pseudo-random bf16 values in
+// +-[1, 2), the way a real kernel presents fresh data to the matrix pipe with every instruction.
+// The second form draws visibly more power, and the chip answers with a lower clock: it is the
+// honest ceiling for a kernel that multiplies real data.
+template <bool RANDOM>
 __global__ __launch_bounds__(512) void ceiling_mfma_kernel(int iters, float *sink, unsigned long long *clocks) {
+  constexpr int NR = RANDOM ? 8 : 1;
   union {
     bf16x8 v;
     unsigned short s[8];
-  } a, b;
+  } a[NR], b[NR];
+  unsigned h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    a.s[e] = (unsigned short)(0x3C00 + (threadIdx.x & 63) + e);
-    b.s[e] = (unsigned short)(0x3B00 + e);
-  }
+  for (int r = 0; r < NR; ++r)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (RANDOM) {
+        h = h * 1664525u + 1013904223u;
+        a[r].s[e] = (unsigned short)(0x3F80u | ((h >> 9) & 0x807Fu));   // sign and mantissa from the hash
+        b[r].s[e] = (unsigned short)(0x3F80u | ((h >> 17) & 0x807Fu));
+      } else {
+        a[r].s[e] = (unsigned short)(0x3C00 + (threadIdx.x & 63) + e);
+        b[r].s[e] = (unsigned short)(0x3B00 + e);
+      }
+    }
   f32x16 acc[4];
 #pragma unroll
   for (int k = 0; k < 4; ++k)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[k][r] = 0.f;
   const unsigned long long c0 = __builtin_readcyclecounter(), w0 = wall_clock64();
-  for (int it = 0; it < iters; ++it) {
+  for (int it = 0; it < iters; it += 2) {  // two rounds per trip: eight MFMAs, every operand register once
 #pragma unroll
-    for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc[k], 0, 0, 0);
+    for (int k = 0; k < 8; ++k)
+      acc[k & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[k % NR].v, b[(k * 3) % NR].v, acc[k & 3], 0, 0, 0);
   }
   const unsigned long long c1 = __builtin_readcyclecounter(), w1 = wall_clock64();
   float s = 0.f;
@@ -73,16 +90,21 @@ using namespace sp;
 
 extern "C" {
 
-int sp_debug_ceiling_mfma(int32_t iters, double *host_flops, void *sink, size_t sink_bytes, void *stream) {
+int sp_debug_ceiling_mfma(int32_t iters, int32_t random_operands, double *host_flops, void *sink,
+                          size_t sink_bytes, void *stream) {
   if (!host_flops || !sink) return fail(SP_ERR_NULL, "sp_debug_ceiling_mfma: NULL argument");
-  if (iters <= 0) return fail(SP_ERR_BAD_SHAPE, "iters=%d must be positive", iters);
+  if (iters <= 0 || iters % 2 != 0) return fail(SP_ERR_BAD_SHAPE, "iters=%d must be positive and even", iters);
   const int cus = cu_count();
   if (cus <= 0) return fail(SP_ERR_HIP, "cannot read the device properties");
   const size_t need = (size_t)cus * sizeof(float) + 16;
   if (sink_bytes < need) return fail(SP_ERR_WORKSPACE, "sink: need %zu bytes, got %zu", need, sink_bytes);
   // layout of sink: two 64-bit clock readings, then one float per workgroup
-  hipLaunchKernelGGL(ceiling_mfma_kernel, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters,
-                     (float *)((char *)sink + 16), (unsigned long long *)sink);
+  if (random_operands)
+    hipLaunchKernelGGL(ceiling_mfma_kernel<true>, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters,
+                       (float *)((char *)sink + 16), (unsigned long long *)sink);
+  else
+    hipLaunchKernelGGL(ceiling_mfma_kernel<false>, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters,
+                       (float *)((char *)sink + 16), (unsigned long long *)sink);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "ceiling launch: %s", hipGetErrorString(e));
   *host_flops = (double)cus * 8.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
