@@ -340,6 +340,50 @@ def test_c5c_8b_shape_decode_batch():
     run_full_compare(W.c5c_decode_8b(batch=32), check_cache=False)
 
 
+def test_c5c_full_size_sampled_sequences():
+    """C5c at full size in the configuration bench.py times (128 sequences U{1024..16384}, 32q/8kv,
+    about 4.7 GB of K/V drawn by torch's seeded GPU generator, the library's own launch shape):
+    every output row of six sampled sequences — the longest, the shortest and four others —
+    against the oracle, which reads those sequences' pages copied back from the device."""
+    import oracle
+    import torch
+    import paper_2507_11830_amd as sp
+
+    w = W.c5c_decode_8b()
+    lens = w.total_lens
+    cache = sp.KVCache.empty(w.num_pages, 8, 128)
+    g = torch.Generator(device="cuda").manual_seed(66)
+    for pool in (cache.k_pages, cache.v_pages):
+        flat = pool.view(-1)
+        slab = 1 << 28
+        for a in range(0, flat.numel(), slab):
+            n = min(slab, flat.numel() - a)
+            flat[a:a + n] = torch.randn(n, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((w.batch, 32, 128), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    bt, sl = dev_i32(w.block_table), dev_i32(lens)
+    mx = int(lens.max())
+    ws = torch.empty(sp.sp_attn_decode_workspace_size(w.batch, mx, 32, 128), dtype=torch.uint8, device="cuda")
+    sp.sp_attn_decode(cache, q, out, sl, bt, mx, float(w.scale), ws)
+    torch.cuda.synchronize()
+    got = W.bf16_bits_to_f64(bits_of(out))
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(5)
+    picks = {int(np.argmax(lens)), int(np.argmin(lens)), *rng.choice(w.batch, size=4, replace=False).tolist()}
+    qb = bits_of(q)
+    worst = 0.0
+    for s_ in sorted(picks):
+        npages = (int(lens[s_]) + 15) // 16
+        pages = torch.from_numpy(w.block_table[s_, :npages].astype(np.int64)).cuda()
+        kp, vp = bits_of(cache.k_pages[pages]), bits_of(cache.v_pages[pages])        # [npages, 8, 16, 128]
+        bt_local = np.arange(npages, dtype=np.int32)[None, :]
+        want = oracle.attn_decode(kp, vp, qb[s_:s_ + 1], np.array([lens[s_]], np.int32), bt_local, w.scale)
+        err = float(np.abs(got[s_] - want[0]).max())
+        print(f"[parity] C5c full size, sequence {s_} (length {int(lens[s_])}): max abs err {err:.5f}", flush=True)
+        worst = max(worst, err)
+    assert worst <= TOL
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_shapes_against_oracle(seed):
     """Seeded random batches (head configuration, head_dim, lengths, cached prefixes, empty
