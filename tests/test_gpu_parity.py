@@ -340,6 +340,51 @@ def test_c5c_8b_shape_decode_batch():
     run_full_compare(W.c5c_decode_8b(batch=32), check_cache=False)
 
 
+def test_decode_step_in_a_hip_graph():
+    """The library only enqueues work (no allocation, no synchronisation), so a decode step can be
+    captured in a HIP graph: capture sp_decode_step once, replay it several times on fresh inputs
+    with ordinary eager work and synchronisations in between, and compare every replay with the
+    eager call and the oracle."""
+    import torch
+    import paper_2507_11830_amd as sp
+
+    lens = np.array([700, 33, 1, 2049, 513])
+    w = custom_workload("graph-step", lens, lens - 1, 8, 1, 128, "decode", seed=95)
+    g, o = GpuRunner(w), OracleRunner(w)
+    steps = list(w.steps())
+    fill, dec = steps[0], steps[1]
+    g.append(fill)
+    o.append(fill)
+    o.append(dec)
+    want = o.attend(dec)
+    k_new, v_new, q = to_dev(dec.k_new), to_dev(dec.v_new), to_dev(dec.q)
+    sl = dev_i32(dec.seq_lens)
+    mx = int(dec.seq_lens.max())
+    ws = torch.empty(sp.sp_attn_decode_workspace_size(w.batch, mx, w.Hq, w.d), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(q)
+    # eager call first: also performs the one-time kernel attribute set-up outside the capture
+    sp.sp_decode_step(g.cache, k_new, v_new, q, out, sl, g.bt, mx, float(w.scale), ws)
+    torch.cuda.synchronize()
+    eager = bits_of(out).copy()
+    assert np.abs(W.bf16_bits_to_f64(eager) - want).max() <= TOL
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sp.sp_decode_step(g.cache, k_new, v_new, q, out, sl, g.bt, mx, float(w.scale), ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        out.zero_()
+        ws.random_(0, 255)                       # stale workspace contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_of(out), eager), f"replay {rep} differs from the eager result"
+    gk, gv = g.cache_bits()
+    assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp)
+
+
 def test_c5c_full_size_sampled_sequences():
     """C5c at full size in the configuration bench.py times (128 sequences U{1024..16384}, 32q/8kv,
     about 4.7 GB of K/V drawn by torch's seeded GPU generator, the library's own launch shape):
