@@ -231,6 +231,40 @@ def extra_big_decode(sp, iters=10):
             "kv_bytes": nbytes}
 
 
+def extra_spec_verify(sp, iters=20):
+    """Speculative-decoding verification on the C3 batch shape: 4 query tokens per sequence (causal
+    inside the chunk) through sp_attn_prefill, which hands such batches to the decode kernels; the
+    general prefill kernel on the same input beside it."""
+    import torch
+    import workloads as W
+
+    w = W.spec_verify()
+    cache = sp.KVCache.empty(w.num_pages, w.Hkv, w.d)
+    bt = _dev_i32(w.block_table)
+    for st in w.steps():
+        cu, ctx = _dev_i32(st.cu_new), _dev_i32(st.ctx_lens)
+        sp.sp_kv_append(cache, _dev_bf16(st.k_new), _dev_bf16(st.v_new), cu, ctx, bt)
+    q = _dev_bf16(st.q)
+    out = torch.empty_like(q)
+    mq, mkv = int(st.new_lens.max()), int(st.seq_lens.max())
+    ms = {}
+    for name, mode in (("short_chunk_path", 0), ("prefill_kernel", 1)):
+        sp.sp_debug_set_tuning("prefill_short_chunk", mode)
+        try:
+            need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], mq, mkv, w.Hq, w.Hkv, w.d)
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+            fn = lambda: sp.sp_attn_prefill(cache, q, out, cu, ctx, bt, mq, mkv, float(w.scale), workspace=ws)
+            _, per = time_phases([fn], iters, 3)
+            ms[name] = per[0]
+        finally:
+            sp.sp_debug_set_tuning("prefill_short_chunk", 0)
+    nbytes = W.decode_bytes(st.seq_lens, w.Hq, w.Hkv, w.d)
+    return {"workload": "speculative verification, 64 sequences x 4 query tokens, 8q/1kv, d=128, contexts U{512..8192}",
+            "ms": ms["short_chunk_path"], "GBps": nbytes / ms["short_chunk_path"] / 1e6,
+            "frac_of_hbm_peak": nbytes / ms["short_chunk_path"] / 1e6 / PEAK_HBM_GBPS, "kv_bytes": nbytes,
+            "ms_general_prefill_kernel": ms["prefill_kernel"]}
+
+
 def extra_chunked_prefill(sp):
     """C4: 32 sequences with lognormal lengths, second half of each prefilled in chunks of <= 512
     tokens against the cached prefix; every step = append + prefill, both timed."""
@@ -251,7 +285,7 @@ def extra_chunked_prefill(sp):
         q = _dev_bf16(st.q)
         out = torch.empty_like(q)
         mq, mkv = int(st.new_lens.max()), int(st.seq_lens.max())
-        need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], w.Hq, w.d)
+        need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], mq, mkv, w.Hq, w.Hkv, w.d)
         ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
         app = lambda: sp.sp_kv_append(cache, k, v, cu, ctx, bt)      # idempotent: same rows, same slots
         att = lambda: sp.sp_attn_prefill(cache, q, out, cu, ctx, bt, mq, mkv, float(w.scale), workspace=ws)
@@ -364,8 +398,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the ceiling kernels and the C5a / C5c / C4 / C5b side measurements")
-    ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5c", "copy"],
-                    help="main = the step described above; c5a / c5c = only that side workload "
+    ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5c", "spec", "copy"],
+                    help="main = the step described above; c5a / c5c / spec = only that side workload "
                          "(used for per-kernel profiles); copy = a plain 1 GiB device copy, the "
                          "known-size kernel the HBM byte counters are calibrated against")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -392,7 +426,7 @@ def main():
                           "GBps_read_plus_write": 2 * n / per[0] / 1e6}))
         return
     if args.workload != "main":
-        fn = extra_long_prefill if args.workload == "c5a" else extra_big_decode
+        fn = {"c5a": extra_long_prefill, "c5c": extra_big_decode, "spec": extra_spec_verify}[args.workload]
         print(json.dumps(fn(sp, iters=args.steps)))
         return
     wp, wd = W.c2_prefill(), W.c3_decode()
@@ -471,7 +505,7 @@ def main():
         res["roofline"]["frac_of_measured_mfma_loop_random_operands"] = tflops / ceil["mfma_loop_random_operands_TFLOPs"]
         res["roofline_decode"]["frac_of_measured_stream_read"] = gbps / ceil["stream_read_GBps"]
         res["other_workloads"] = [extra_long_prefill(sp), extra_big_decode(sp), extra_chunked_prefill(sp),
-                                  extra_shift_decode(sp), extra_head_exchange(sp)]
+                                  extra_shift_decode(sp), extra_spec_verify(sp), extra_head_exchange(sp)]
         for o in res["other_workloads"]:
             if "TFLOPs" in o:
                 o["frac_of_measured_mfma_loop"] = o["TFLOPs"] / ceil["mfma_loop_TFLOPs"]

@@ -94,6 +94,11 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  *                   log-sum-exp combine pass, which it does for batches of few query tokens on
  *                   long cached prefixes; with NULL / 0 (or less than that) it uses fewer
  *                   pieces or none.  The result is the same up to fp32 summation order.
+ *                   Batches whose chunks are all a few tokens long (max_q_len times the query
+ *                   heads per KV head <= 32: the verification step of speculative decoding)
+ *                   are served, when the workspace allows, by the decode kernels —
+ *                   bandwidth-bound, all of a sequence's query tokens share one read of its
+ *                   keys.
  * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax.
  */
 int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
@@ -138,9 +143,12 @@ int sp_decode_step(const sp_cache_desc *cache, const void *k_new, const void *v_
                    size_t workspace_bytes, void *stream);
 
 /* Bytes of workspace for the given host-side shape: what sp_attn_decode requires, and what lets
- * sp_attn_prefill split key ranges (0 when the batch has too many query rows for that to pay). */
-size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens,
-                                      int32_t num_q_heads, int32_t head_dim);
+ * sp_attn_prefill split key ranges or take its short-chunk path (0 when neither would be used:
+ * too many query rows for it to pay).  max_q_len / max_kv_len are the hints later passed to
+ * sp_attn_prefill; the size is monotone in neither, so ask again when they change. */
+size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens, int32_t max_q_len,
+                                      int32_t max_kv_len, int32_t num_q_heads,
+                                      int32_t num_kv_heads, int32_t head_dim);
 size_t sp_attn_decode_workspace_size(int32_t batch, int32_t max_seq_len, int32_t num_q_heads,
                                      int32_t head_dim);
 
@@ -184,6 +192,9 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  *                   heuristic on the grid size), 1 (neighbouring query columns, shared key
  *                   tiles), 2 (same query columns, alternate key tiles, merged at the end).
  *                   Both give the same result up to fp32 summation order.
+ *   "prefill_short_chunk" 0 (built-in choice: batches of short chunks go to the decode
+ *                   kernels when the workspace allows) or 1 (never; always the prefill kernel).
+ *                   Changes what sp_attn_prefill_workspace_size returns.
  * Returns SP_OK, SP_ERR_NULL or SP_ERR_UNSUPPORTED (unknown key / value out of range).
  */
 int sp_debug_set_tuning(const char *key, int32_t value);

@@ -71,7 +71,7 @@ def lib() -> ctypes.CDLL:
         L.sp_ulysses_pack.restype = ctypes.c_int
         L.sp_ulysses_unpack.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         L.sp_ulysses_unpack.restype = ctypes.c_int
-        L.sp_attn_prefill_workspace_size.argtypes = [i32, i32, i32, i32]
+        L.sp_attn_prefill_workspace_size.argtypes = [i32, i32, i32, i32, i32, i32, i32]
         L.sp_attn_prefill_workspace_size.restype = sz
         L.sp_attn_decode_workspace_size.argtypes = [i32, i32, i32, i32]
         L.sp_attn_decode_workspace_size.restype = sz
@@ -173,8 +173,10 @@ def sp_attn_decode_workspace_size(batch: int, max_seq_len: int, num_q_heads: int
     return lib().sp_attn_decode_workspace_size(batch, max_seq_len, num_q_heads, head_dim)
 
 
-def sp_attn_prefill_workspace_size(batch: int, total_q_tokens: int, num_q_heads: int, head_dim: int) -> int:
-    return lib().sp_attn_prefill_workspace_size(batch, total_q_tokens, num_q_heads, head_dim)
+def sp_attn_prefill_workspace_size(batch: int, total_q_tokens: int, max_q_len: int, max_kv_len: int,
+                                   num_q_heads: int, num_kv_heads: int, head_dim: int) -> int:
+    return lib().sp_attn_prefill_workspace_size(batch, total_q_tokens, max_q_len, max_kv_len, num_q_heads,
+                                                num_kv_heads, head_dim)
 
 
 def sp_attn_decode(cache: KVCache, q, out, seq_lens, block_table, max_seq_len: int, scale: float,

@@ -150,11 +150,14 @@ int sp_ulysses_unpack(const void *recv, void *y, int32_t tokens, int32_t num_hea
   return ulysses_common(false, recv, y, tokens, num_heads, head_dim, world, stream);
 }
 
-size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens, int32_t num_q_heads,
+size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens, int32_t max_q_len,
+                                      int32_t max_kv_len, int32_t num_q_heads, int32_t num_kv_heads,
                                       int32_t head_dim) {
-  (void)batch;
-  if (total_q_tokens <= 0 || num_q_heads <= 0 || head_dim <= 0) return 0;
-  return prefill_workspace_bytes(total_q_tokens, num_q_heads, head_dim);
+  if (batch <= 0 || total_q_tokens <= 0 || num_q_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 ||
+      num_q_heads % num_kv_heads != 0)
+    return 0;
+  return prefill_workspace_bytes(batch, total_q_tokens, max_q_len, max_kv_len, num_q_heads, num_kv_heads,
+                                 head_dim);
 }
 
 size_t sp_attn_decode_workspace_size(int32_t batch, int32_t max_seq_len, int32_t num_q_heads,
@@ -212,6 +215,11 @@ int sp_debug_set_tuning(const char *key, int32_t value) {
   if (!strcmp(key, "prefill_split")) {
     if (value < 0 || value > 2) return fail(SP_ERR_UNSUPPORTED, "prefill_split=%d (0, 1 or 2)", value);
     set_prefill_split(value);
+    return SP_OK;
+  }
+  if (!strcmp(key, "prefill_short_chunk")) {
+    if (value < 0 || value > 1) return fail(SP_ERR_UNSUPPORTED, "prefill_short_chunk=%d (0 or 1)", value);
+    set_prefill_short_chunk(value);
     return SP_OK;
   }
   return fail(SP_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);

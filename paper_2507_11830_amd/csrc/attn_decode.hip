@@ -28,9 +28,11 @@ struct DecodeArgs {
   const char *k_pages, *v_pages, *q;
   const char *k_new, *v_new;  // APPEND kernels: this step's K/V rows, bf16 [batch][Hkv][D]
   const int32_t *seq_lens, *block_table;
-  float *part_o;   // [batch][Hq][nsplit][D]
-  float *part_ml;  // [batch][Hq][nsplit][2]  (m in log2 units, l)
+  const int32_t *cu_q, *ctx_lens;  // MQ kernels: query-token prefix sums [batch + 1], cached lengths [batch]
+  float *part_o;   // [row][nsplit][D], row = token * Hq + head (one token per sequence unless MQ)
+  float *part_ml;  // [row][nsplit][2]  (m in log2 units, l)
   int max_pages, num_pages, Hq, Hkv, group, geff, n_hgroups, chunk, nsplit;
+  int q_cap;  // MQ kernels: query tokens per tile (32 / geff)
   float sl2e;
   float tau;  // lazy-rescale threshold in raw score units (8 / sl2e)
 };
@@ -38,16 +40,19 @@ struct DecodeArgs {
 static int g_chunk_override = 0;  // tuning hooks (sp_debug_set_tuning), 0 = heuristic
 static int g_ring_override = 0;
 
-static int pick_chunk(int batch, int num_q_heads, int max_seq_len) {
+static int pick_chunk(int batch, int num_q_heads, int max_seq_len, int q_len = 1) {
   if (g_chunk_override > 0) return g_chunk_override;
   // Longer splits amortise a wave's fixed costs (first loads, its partial, the combine pass),
   // shorter ones fill and balance the chip: aim for a few waves per CU.  Estimate with ~8 query
   // heads per split and a mean length of half the maximum; only host-side shape is used, so
-  // the workspace size is known without reading device memory.
+  // the workspace size is known without reading device memory.  With q_len query tokens per
+  // sequence a split's partial is q_len times larger against the same keys read, so the balance
+  // moves towards longer splits.
+  const long enough = 512 / q_len > 64 ? 512 / q_len : 64;
   int chunk = kDecMaxChunk;
   while (chunk > kDecMinChunk) {
     long est = (long)batch * ((num_q_heads + 7) / 8) * ((long)max_seq_len / 2) / chunk;
-    if (est >= 512) break;
+    if (est >= enough) break;
     chunk /= 2;
   }
   return chunk;
@@ -85,8 +90,16 @@ __device__ __forceinline__ void wait_vmcnt() {
 // cache yet but in k_new / v_new.  The wave whose range holds that position writes the row into
 // its page (for later steps) and patches it into its own LDS copy of the last block (for this
 // step), so the separate append launch in front of every decode step disappears.
-template <int D, int NB, bool APPEND>
+//
+// MQ = true serves short query chunks (speculative-decoding verification: a handful of draft
+// tokens per sequence on a long cached prefix, causal inside the chunk; the paper combines Shift
+// Parallelism with speculative decoding in its "Arctic Inference" section).  The 32 tile columns
+// then hold q_cap tokens x geff heads, each column with its own causal limit, the inputs are the
+// ragged ones of sp_attn_prefill (cu_q, ctx_lens; the chunk's K/V rows are in the cache already),
+// and K/V are still read once for all of them.
+template <int D, int NB, bool APPEND, bool MQ>
 __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
+  static_assert(!(APPEND && MQ), "the fused append is a single-token step");
   using G = TileGeom<D>;
   using Z = SwzTile<D>;
   constexpr int ROWB = D * 2;           // bytes of one K or V row
@@ -116,12 +129,34 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   // Page ids of the wave's keys, one per lane (<= 64 pages); later broadcast by readlane.
   // Entries past the sequence end are fetched too (index clamped to the table) and never used.
   int my_page = bt_row[min((kv0 >> 4) + lane, a.max_pages - 1)];
+  // Column -> (query token, head) of the tile, and the row of q / out / the partials it stands for.
+  int L, ctx = 0, kv_end, lim_min = 0, lim_col = 0;
+  bool col_valid;
+  long row_col;
+  if (MQ) {
+    const int tok0 = a.cu_q[seq];
+    const int qn = a.cu_q[seq + 1] - tok0;
+    ctx = a.ctx_lens[seq];
+    const int t = col / a.geff, h_col = col - t * a.geff;  // the host made sure that qn <= q_cap
+    if (qn <= 0) return;  // no query token: no output row, no partial
+    col_valid = t < min(qn, a.q_cap) && h_col < ncols;
+    row_col = (long)(tok0 + t) * a.Hq + head0 + h_col;
+    L = ctx + qn;
+    kv_end = L;          // keys visible to the chunk's last token
+    lim_min = ctx + 1;   // keys visible to its first token
+    lim_col = col_valid ? ctx + t + 1 : kv_end;
+  } else {
+    col_valid = col < ncols;
+    row_col = (long)seq * a.Hq + head0 + col;
+    L = 0;  // loaded below, after the query rows are requested
+    kv_end = 0;
+  }
   bf16x8 qreg[G::kDSteps];
   {
-    const char *qrow = a.q + ((long)seq * a.Hq + head0 + col) * (D * 2);
+    const char *qrow = a.q + row_col * (D * 2);
 #pragma unroll
     for (int s = 0; s < G::kDSteps; ++s) {
-      if (col < ncols) {
+      if (col_valid) {
         qreg[s] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * s + 16 * half);
       } else {
         u32x4 z = {0, 0, 0, 0};
@@ -138,14 +173,16 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     knew = *reinterpret_cast<const u32x4 *>(a.k_new + noff);
     vnew = *reinterpret_cast<const u32x4 *>(a.v_new + noff);
   }
-  const int L = a.seq_lens[seq];
-  if (kv0 >= L) {  // nothing to attend to: an empty partial, so the combine pass needs no lengths
-    if (lane < ncols)
-      *reinterpret_cast<f32x2 *>(a.part_ml + (((long)seq * a.Hq + head0 + lane) * a.nsplit + split) * 2) =
-          (f32x2){-INFINITY, 0.f};
+  if (!MQ) {
+    L = a.seq_lens[seq];
+    kv_end = L;
+  }
+  if (kv0 >= kv_end) {  // nothing to attend to: an empty partial, so the combine pass needs no lengths
+    if (lane < 32 && col_valid)
+      *reinterpret_cast<f32x2 *>(a.part_ml + (row_col * a.nsplit + split) * 2) = (f32x2){-INFINITY, 0.f};
     return;
   }
-  const int kv1 = min(L, kv0 + a.chunk);
+  const int kv1 = min(kv_end, kv0 + a.chunk);
   const int nb = (kv1 - kv0 + 31) >> 5;  // blocks of this wave, >= 1
   my_page = min(max(my_page, 0), a.num_pages - 1);  // bad metadata must not become a wild load
 
@@ -218,7 +255,9 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m = -INFINITY, l = 0.f;
+  // MQ: a column may find every key of the wave's first blocks behind its causal limit; a
+  // finite floor keeps exp2(m - m) defined for it (the partial is written as empty if l stays 0).
+  float m = MQ ? -1e30f : -INFINITY, l = 0.f;
 
 #pragma unroll
   for (int bi = 0; bi < NB - 1; ++bi)
@@ -268,7 +307,16 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] += sacc1[r];
-    if (base + 32 > kv1) {
+    if (MQ) {
+      if (base + 32 > min(lim_min, kv1)) {  // the block reaches into the chunk: per-column causal limit
+        const int lim = min(lim_col, kv1);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
+          if (kv >= lim) sacc[r] = -INFINITY;
+        }
+      }
+    } else if (base + 32 > kv1) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
@@ -323,8 +371,8 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
 
   // ---- the wave's partial: un-normalised o, m in log2 units, l
   l += other_half(l);
-  if (col < ncols) {
-    const long pidx = ((long)seq * a.Hq + head0 + col) * a.nsplit + split;
+  if (col_valid) {
+    const long pidx = row_col * a.nsplit + split;
     float *po = a.part_o + pidx * D;
 #pragma unroll
     for (int db = 0; db < G::kDBlocks; ++db)
@@ -332,7 +380,8 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
       for (int r4 = 0; r4 < 4; ++r4)
         *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * r4 + 4 * half) =
             (f32x4){o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
-    if (half == 0) *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){m * a.sl2e, l};
+    if (half == 0)
+      *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){MQ && l == 0.f ? -INFINITY : m * a.sl2e, l};
   }
 }
 
@@ -476,11 +525,11 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
   return SP_OK;
 }
 
-template <int D, int NB, bool APPEND>
+template <int D, int NB, bool APPEND, bool MQ = false>
 static int launch_split(const DecodeArgs &a, int batch, hipStream_t stream) {
   static bool attr_set = false;  // benign if two threads race
   constexpr int smem = NB * 2 * 32 * D * 2;
-  auto fn = decode_split_kernel<D, NB, APPEND>;
+  auto fn = decode_split_kernel<D, NB, APPEND, MQ>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return fail(SP_ERR_HIP, "decode smem attribute: %s", hipGetErrorString(e));
@@ -506,6 +555,71 @@ static int launch_decode_d(DecodeArgs &a, char *out, int batch, hipStream_t stre
   return launch_combine(a.part_o, a.part_ml, out, (long)batch * a.Hq, a.nsplit, D, stream);
 }
 
+// Head-group geometry shared by the single-token and the short-chunk launches.
+static void set_head_groups(DecodeArgs &a, int num_q_heads, int num_kv_heads) {
+  a.Hq = num_q_heads;
+  a.Hkv = num_kv_heads;
+  a.group = num_q_heads / num_kv_heads;
+  a.geff = a.group < 32 ? a.group : 32;
+  if (a.group % a.geff != 0) a.geff = 1;  // odd large groups: one head per tile
+  a.n_hgroups = num_q_heads / a.geff;
+  a.q_cap = 32 / a.geff;
+}
+
+// ---- short query chunks (sp_attn_prefill with a few tokens per sequence) on the split kernel
+// A chunk qualifies when its tokens x the heads of a tile fit the 32 tile columns.  (Longer chunks
+// on several tiles per sequence re-read the keys once per tile and measured slower than the
+// prefill kernel.)
+static bool multi_shape(int max_q_len, int num_q_heads, int num_kv_heads, DecodeArgs *a) {
+  set_head_groups(*a, num_q_heads, num_kv_heads);
+  return max_q_len > 0 && max_q_len <= a->q_cap;
+}
+
+size_t decode_multi_workspace_bytes(int batch, int total_q, int max_q_len, int max_kv_len, int num_q_heads,
+                                    int num_kv_heads, int head_dim) {
+  DecodeArgs a;
+  if (max_kv_len <= 0 || total_q <= 0 || !multi_shape(max_q_len, num_q_heads, num_kv_heads, &a)) return 0;
+  if ((long)batch * a.n_hgroups > 65535) return 0;
+  const int chunk = pick_chunk(batch, num_q_heads, max_kv_len, max_q_len);
+  const size_t nsplit = (size_t)(max_kv_len + chunk - 1) / chunk;
+  return (size_t)total_q * num_q_heads * nsplit * (head_dim + 2) * sizeof(float);
+}
+
+// Returns SP_OK after launching, or 1 when the shape or the workspace does not qualify (the caller
+// then runs the general prefill kernel).
+int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
+                        const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
+                        int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
+                        void *workspace, size_t workspace_bytes, hipStream_t stream) {
+  const size_t need = decode_multi_workspace_bytes(batch, total_q, max_q_len, max_kv_len, num_q_heads,
+                                                   c.num_kv_heads, c.head_dim);
+  if (need == 0 || !workspace || workspace_bytes < need) return 1;
+  DecodeArgs a;
+  multi_shape(max_q_len, num_q_heads, c.num_kv_heads, &a);
+  a.k_pages = (const char *)c.k_pages;
+  a.v_pages = (const char *)c.v_pages;
+  a.k_new = a.v_new = nullptr;
+  a.q = (const char *)q;
+  a.seq_lens = nullptr;
+  a.cu_q = cu_q;
+  a.ctx_lens = ctx_lens;
+  a.block_table = block_table;
+  a.max_pages = max_pages;
+  a.num_pages = c.num_pages;
+  a.sl2e = scale * 1.44269504088896340736f;
+  a.tau = 8.0f / a.sl2e;
+  a.chunk = pick_chunk(batch, num_q_heads, max_kv_len, max_q_len);
+  a.nsplit = (max_kv_len + a.chunk - 1) / a.chunk;
+  a.part_o = (float *)workspace;
+  a.part_ml = a.part_o + (size_t)total_q * num_q_heads * a.nsplit * c.head_dim;
+  int rc = c.head_dim == 128 ? launch_split<128, 2, false, true>(a, batch, stream)
+                             : launch_split<64, 2, false, true>(a, batch, stream);
+  if (rc != SP_OK) return rc;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SP_ERR_HIP, "short-chunk split launch: %s", hipGetErrorString(e));
+  return launch_combine(a.part_o, a.part_ml, out, (long)total_q * num_q_heads, a.nsplit, c.head_dim, stream);
+}
+
 int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
                   const int32_t *seq_lens, const int32_t *block_table, int batch, int max_pages,
                   int max_seq_len, int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
@@ -518,15 +632,11 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
   a.v_new = (const char *)v_new;
   a.q = (const char *)q;
   a.seq_lens = seq_lens;
+  a.cu_q = a.ctx_lens = nullptr;
   a.block_table = block_table;
   a.max_pages = max_pages;
   a.num_pages = c.num_pages;
-  a.Hq = num_q_heads;
-  a.Hkv = c.num_kv_heads;
-  a.group = num_q_heads / c.num_kv_heads;
-  a.geff = a.group < 32 ? a.group : 32;
-  if (a.group % a.geff != 0) a.geff = 1;  // odd large groups: one head per tile
-  a.n_hgroups = num_q_heads / a.geff;
+  set_head_groups(a, num_q_heads, c.num_kv_heads);
   a.sl2e = scale * 1.44269504088896340736f;
   a.tau = 8.0f / a.sl2e;
   if (max_seq_len <= 0) {

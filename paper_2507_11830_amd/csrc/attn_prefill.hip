@@ -531,6 +531,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 
 static int g_split_mode = 0;
 static int g_kv_splits = 0;
+static int g_short_chunk_mode = 0;
+void set_prefill_short_chunk(int mode) { g_short_chunk_mode = mode; }
 void set_prefill_split(int mode) { g_split_mode = mode; }
 void set_prefill_kv_splits(int n) { g_kv_splits = n; }
 
@@ -546,10 +548,15 @@ static int kv_split_cap(long rows) {
   return (int)(cap < 1 ? 1 : cap > kMaxKvSplits ? kMaxKvSplits : cap);
 }
 
-size_t prefill_workspace_bytes(int total_q_tokens, int num_q_heads, int head_dim) {
+size_t prefill_workspace_bytes(int batch, int total_q_tokens, int max_q_len, int max_kv_len, int num_q_heads,
+                               int num_kv_heads, int head_dim) {
   const long rows = (long)total_q_tokens * num_q_heads;
   const int cap = kv_split_cap(rows);
-  return cap >= 2 ? (size_t)rows * cap * (head_dim + 2) * sizeof(float) : 0;
+  const size_t pieces = cap >= 2 ? (size_t)rows * cap * (head_dim + 2) * sizeof(float) : 0;
+  const size_t shortq = g_short_chunk_mode == 1 ? 0
+                                                : decode_multi_workspace_bytes(batch, total_q_tokens, max_q_len, max_kv_len,
+                                                                               num_q_heads, num_kv_heads, head_dim);
+  return pieces > shortq ? pieces : shortq;
 }
 
 // Launches one prefill kernel instantiation with `cols` query columns per workgroup.
@@ -589,6 +596,13 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                    int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
                    void *workspace, size_t workspace_bytes, hipStream_t stream) {
+  if (g_short_chunk_mode != 1) {
+    // Every chunk is a few tokens long: the bandwidth-bound split kernel of the decode path reads
+    // each sequence's keys once for all of its query tokens.
+    int rc = launch_decode_multi(c, q, out, cu_q, ctx_lens, block_table, batch, max_pages, total_q, max_q_len,
+                                 max_kv_len, num_q_heads, scale, workspace, workspace_bytes, stream);
+    if (rc != 1) return rc;
+  }
   PrefillArgs a;
   a.k_pages = (const char *)c.k_pages;
   a.v_pages = (const char *)c.v_pages;

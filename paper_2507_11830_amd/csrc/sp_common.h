@@ -33,7 +33,8 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                    int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
                    void *workspace, size_t workspace_bytes, hipStream_t stream);
-size_t prefill_workspace_bytes(int total_q_tokens, int num_q_heads, int head_dim);
+size_t prefill_workspace_bytes(int batch, int total_q_tokens, int max_q_len, int max_kv_len, int num_q_heads,
+                               int num_kv_heads, int head_dim);
 
 // [T_loc][H][d] <-> [P][T_loc][H/P][d] (pack = to the blocked side), bf16 elements.
 int launch_ulysses(bool pack, const void *src, void *dst, int T_loc, int H, int d, int P, hipStream_t stream);
@@ -42,6 +43,7 @@ int launch_ulysses(bool pack, const void *src, void *dst, int T_loc, int H, int 
 void set_decode_chunk(int chunk);
 void set_decode_ring(int slots);   // LDS ring depth of the decode split kernel: 0 heuristic, 2..4
 void set_prefill_kv_splits(int n);  // pieces a query tile's key range is cut into: 0 heuristic, 1..16
+void set_prefill_short_chunk(int mode);  // 0 heuristic, 1 short query chunks stay on the prefill kernel
 void set_prefill_split(int mode);  // 0 heuristic, 1 never split the key range over the wave groups, 2 always
 
 // Log-sum-exp merge of per-split partials: part_o [rows][nsplit][head_dim] fp32 un-normalised,
@@ -56,5 +58,15 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
                   const int32_t *seq_lens, const int32_t *block_table, int batch, int max_pages,
                   int max_seq_len, int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
                   hipStream_t stream);
+
+// Short query chunks (a few tokens per sequence on long prefixes) on the decode split kernel:
+// same arguments as launch_prefill.  Returns 1 without launching anything when the shape or the
+// workspace does not qualify; decode_multi_workspace_bytes is 0 for shapes that never qualify.
+size_t decode_multi_workspace_bytes(int batch, int total_q, int max_q_len, int max_kv_len, int num_q_heads,
+                                    int num_kv_heads, int head_dim);
+int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
+                        const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
+                        int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
+                        void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace sp

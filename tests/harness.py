@@ -51,7 +51,8 @@ class GpuRunner:
         q = to_dev(st.q)
         out = torch.empty_like(q)
         if st.kind == "prefill":
-            need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], w.Hq, w.d) if self.prefill_workspace else 0
+            need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], int(st.new_lens.max()),
+                                                     int(st.seq_lens.max()), w.Hq, w.Hkv, w.d) if self.prefill_workspace else 0
             ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
             sp.sp_attn_prefill(self.cache, q, out, dev_i32(st.cu_new), dev_i32(st.ctx_lens), self.bt,
                                int(st.new_lens.max()), int(st.seq_lens.max()), float(w.scale), workspace=ws)

@@ -65,14 +65,26 @@ def test_workspace_size_is_host_only_arithmetic(built_lib):
 def test_prefill_workspace_size_is_host_only_arithmetic(built_lib):
     f = built_lib.sp_attn_prefill_workspace_size
     f.restype = ctypes.c_size_t
-    f.argtypes = [ctypes.c_int32] * 4
-    assert f(4, 0, 8, 128) == 0
+    f.argtypes = [ctypes.c_int32] * 7   # batch, total_q, max_q_len, max_kv_len, Hq, Hkv, head_dim
+    assert f(4, 0, 0, 100, 8, 1, 128) == 0
     # few query rows: room for up to 16 pieces of (head_dim + 2) fp32 per (token, head)
-    assert f(4, 100, 8, 128) == 100 * 8 * 16 * 130 * 4
+    assert f(4, 100, 25, 4000, 8, 1, 128) == 100 * 8 * 16 * 130 * 4
     # many query rows: key ranges are never cut, no workspace asked for
-    assert f(4, 32768, 8, 128) == 0
-    small, big = f(1, 1000, 8, 128), f(1, 8000, 8, 128)
+    assert f(4, 32768, 8192, 8192, 8, 1, 128) == 0
+    small, big = f(1, 1000, 1000, 1000, 8, 1, 128), f(1, 8000, 8000, 8000, 8, 1, 128)
     assert small > 0 and big > 0 and big <= 2 * (1 << 17) * 130 * 4
+    # chunks of a few tokens (the decode kernels serve them): one partial per 128..1024 keys and row,
+    # however many rows there are
+    rows = 128 * 4 * 32
+    short = f(128, 128 * 4, 4, 16384, 32, 8, 128)
+    assert rows * 16 * 130 * 4 <= short <= rows * 128 * 130 * 4
+    # ... unless that path is switched off
+    import paper_2507_11830_amd as sp
+    sp.sp_debug_set_tuning("prefill_short_chunk", 1)
+    try:
+        assert f(128, 128 * 4, 4, 16384, 32, 8, 128) == rows * 8 * 130 * 4   # the key-range pieces only
+    finally:
+        sp.sp_debug_set_tuning("prefill_short_chunk", 0)
 
 
 def test_argument_validation_needs_no_gpu(built_lib):
@@ -127,7 +139,9 @@ def test_tuning_keys_are_validated(built_lib):
         assert L.sp_debug_set_tuning(b"decode_ring", v) == want
     for v, want in [(1, sp.SP_OK), (16, sp.SP_OK), (17, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"prefill_kv_splits", v) == want
-    for key in (b"decode_chunk", b"decode_ring", b"prefill_split", b"prefill_kv_splits"):
+    for v, want in [(1, sp.SP_OK), (2, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
+        assert L.sp_debug_set_tuning(b"prefill_short_chunk", v) == want
+    for key in (b"decode_chunk", b"decode_ring", b"prefill_split", b"prefill_kv_splits", b"prefill_short_chunk"):
         assert L.sp_debug_set_tuning(key, 0) == sp.SP_OK
 
 

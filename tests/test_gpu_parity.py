@@ -210,6 +210,58 @@ def test_short_query_chunks_on_long_prefixes():
     run_full_compare(custom_workload("spec-verify", ctx + new, ctx, 8, 1, 128, "prefill", seed=53))
 
 
+SHORT_CHUNK_CASES = {
+    # name: (Hq, Hkv, d, new tokens per sequence, cached tokens per sequence)
+    # 8 heads per KV head: 4 tokens fill the 32-column tile
+    "g8": (8, 1, 128, [4, 4, 2, 3, 1, 3, 0, 4], [1000, 37, 4095, 512, 16, 0, 99, 2300]),
+    # the chunk straddles a split boundary (multiples of 128): columns whose causal limit lies
+    # before the split's first key see no key at all in it
+    "g8-straddle": (8, 1, 128, [4, 4, 4, 4, 3, 2], [126, 127, 125, 253, 1022, 511]),
+    "g4-8b": (32, 8, 128, [8, 3, 6, 1], [700, 2049, 64, 130]),
+    "g8x2": (16, 2, 128, [4, 2, 3], [513, 300, 77]),
+    "g1": (4, 4, 128, [32, 9, 1], [200, 1500, 33]),
+    "g5": (5, 1, 128, [6, 1, 5], [400, 129, 1000]),      # 6 tokens x 5 heads = 30 of 32 columns
+    "d64": (8, 2, 64, [8, 5, 2], [333, 1025, 0]),
+    "fresh": (8, 1, 128, [4, 3, 1], [0, 0, 0]),          # nothing cached: a prefill of a few tokens
+}
+
+
+@pytest.mark.parametrize("short_path", [0, 1])
+@pytest.mark.parametrize("case", sorted(SHORT_CHUNK_CASES))
+def test_short_chunks_on_both_kernel_paths(case, short_path):
+    """Batches of a few query tokens per sequence (speculative-decoding verification): by default
+    the decode kernels serve them when tokens x heads of a KV head fit the 32 tile columns
+    (per-column causal limit, split-K + combine); the tuning key forces the general prefill kernel.
+    Both against the oracle."""
+    import paper_2507_11830_amd as sp
+
+    Hq, Hkv, d, new, ctx = SHORT_CHUNK_CASES[case]
+    new, ctx = np.array(new), np.array(ctx)
+    sp.sp_debug_set_tuning("prefill_short_chunk", short_path)
+    try:
+        run_full_compare(custom_workload(f"short-{case}-{short_path}", ctx + new, ctx, Hq, Hkv, d, "prefill", seed=61))
+    finally:
+        sp.sp_debug_set_tuning("prefill_short_chunk", 0)
+
+
+def test_spec_verify_bench_shape_full_size():
+    """The 64-sequence, 4-token verification batch bench.py times, every output element."""
+    run_full_compare(W.spec_verify(), check_cache=False)
+
+
+def test_short_chunks_with_small_splits():
+    """128-key splits put a split boundary inside or next to every chunk."""
+    import paper_2507_11830_amd as sp
+
+    new = np.array([4, 4, 4, 4, 4, 4, 4, 4])
+    ctx = np.array([124, 125, 126, 127, 128, 129, 380, 1])
+    sp.sp_debug_set_tuning("decode_chunk", 128)
+    try:
+        run_full_compare(custom_workload("short-128", ctx + new, ctx, 8, 1, 128, "prefill", seed=62))
+    finally:
+        sp.sp_debug_set_tuning("decode_chunk", 0)
+
+
 def test_decode_with_empty_sequences():
     import torch
     import paper_2507_11830_amd as sp

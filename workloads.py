@@ -197,6 +197,24 @@ def c3_decode(batch: int = 64, lo: int = 512, hi: int = 8192, Hq: int = 8, Hkv: 
     return Workload(name, Hq, Hkv, d, pool, bt, total, gen)
 
 
+def spec_verify(batch: int = 64, lo: int = 512, hi: int = 8192, q_len: int = 4, Hq: int = 8, Hkv: int = 1,
+                d: int = 128, n: int = 7) -> Workload:
+    """The decode batch of c3_decode with q_len query tokens per sequence instead of one (a
+    speculative-decoding verification step: the last accepted token plus q_len - 1 draft tokens,
+    causal inside the chunk).  The cache is filled with L - q_len tokens, then one chunk step
+    appends the q_len tokens and attends."""
+    s_len, s_bt, s_val = _seeds(n)
+    total = _rng(s_len).integers(lo, hi + 1, size=batch).astype(np.int32)
+    bt, pool = make_block_table(_rng(s_bt), total)
+
+    def gen():
+        rng = _rng(s_val)
+        yield _chunk_step(rng, "fill", total - q_len, np.zeros(batch), Hq, Hkv, d)
+        yield _chunk_step(rng, "prefill", np.full(batch, q_len), total - q_len, Hq, Hkv, d)
+
+    return Workload(f"spec_verify_q{q_len}", Hq, Hkv, d, pool, bt, total, gen)
+
+
 def c4_lengths(batch: int = 32, median: float = 1500.0, sigma: float = 1.0, lo: int = 64,
                hi: int = 8192) -> np.ndarray:
     s_len, _, _ = _seeds(4)
