@@ -192,6 +192,10 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  *                   heuristic on the grid size), 1 (neighbouring query columns, shared key
  *                   tiles), 2 (same query columns, alternate key tiles, merged at the end).
  *                   Both give the same result up to fp32 summation order.
+ *   "prefill_order" which work item (sequence, query tile) a prefill workgroup takes: 0 (built-in
+ *                   choice), 1 (by launch index: last query tiles of all sequences first), 2 (the
+ *                   workgroup with the r-th launch index takes the r-th heaviest item; batches of
+ *                   up to 256 sequences).  Same result bit for bit.
  *   "prefill_short_chunk" 0 (built-in choice: batches of short chunks go to the decode
  *                   kernels when the workspace allows) or 1 (never; always the prefill kernel).
  *                   Changes what sp_attn_prefill_workspace_size returns.

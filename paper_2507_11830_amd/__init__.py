@@ -55,6 +55,11 @@ def lib() -> ctypes.CDLL:
             raise ImportError(
                 f"{LIB_PATH} is missing: run `python -m paper_2507_11830_amd.build` "
                 "(or __graft_entry__.build()) first; there is no non-HIP fallback")
+        # PyTorch ships its own HIP runtime and owns the device buffers this binding is handed: it
+        # has to be in the process before the library binds to a runtime.  Loaded the other way
+        # round, the library's first launch fails with "no ROCm-capable device is detected".
+        import torch  # noqa: F401
+
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         cd = ctypes.POINTER(sp_cache_desc)

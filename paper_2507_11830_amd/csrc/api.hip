@@ -217,6 +217,11 @@ int sp_debug_set_tuning(const char *key, int32_t value) {
     set_prefill_split(value);
     return SP_OK;
   }
+  if (!strcmp(key, "prefill_order")) {
+    if (value < 0 || value > 2) return fail(SP_ERR_UNSUPPORTED, "prefill_order=%d (0, 1 or 2)", value);
+    set_prefill_order(value);
+    return SP_OK;
+  }
   if (!strcmp(key, "prefill_short_chunk")) {
     if (value < 0 || value > 1) return fail(SP_ERR_UNSUPPORTED, "prefill_short_chunk=%d (0 or 1)", value);
     set_prefill_short_chunk(value);

@@ -60,7 +60,102 @@ struct PrefillArgs {
   // un-normalised partials [row][kv_splits][D] and (max in log2 units, sum) [row][kv_splits][2]
   float *part_o, *part_ml;
   int kv_splits;
+  int batch;
+  int ranked;  // workgroups take their work items heaviest first (ranked_item below)
 };
+
+// Inclusive prefix sum over the 64 lanes (gfx9 DPP: shifts inside rows of 16, then the two row
+// broadcasts); lane 63 ends up with the total.
+__device__ __forceinline__ int wave_scan_incl(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, false);  // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, false);  // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, false);  // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, false);  // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2 and 3
+  return x;
+}
+__device__ __forceinline__ int wave_total(int x) { return __builtin_amdgcn_readlane(wave_scan_incl(x), 63); }
+
+// Ranked dispatch.  The hardware starts workgroups in linear id order and a CU takes the next one
+// when it has room, so the launch is a list schedule and its makespan depends on the list's
+// order: longest items first is the classic 4/3 rule, and a chunked-prefill batch whose sequences
+// sit on cached prefixes of very different lengths is far from it in (tile, sequence) order (the
+// early query tiles of the sequence with the longest prefix are as heavy as anything in the batch
+// but would start last).  Here the workgroup with linear id r finds the r-th heaviest (sequence,
+// query tile) item by itself: the weight of an item is its number of visible keys in 64-key
+// tiles, the number of items at least as heavy as x is a sum over sequences of a closed form, so
+// a binary search over x and one prefix sum over the ties select the item in a few hundred
+// instructions, from the same two length arrays every workgroup reads anyway.  One sequence per
+// lane and slot: batches of up to 64 * kRankSlots sequences.
+constexpr int kRankSlots = 4;
+
+__device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift, int r, int lane, int *seq_out,
+                                            int *tile_out) {
+  const int tpt = 1 << tpt_shift;
+  int c[kRankSlots], q[kRankSlots], nt[kRankSlots];
+  const int nslot = (a.batch + 63) >> 6;  // uniform
+#pragma unroll
+  for (int u = 0; u < kRankSlots; ++u) {
+    const int s = u * 64 + lane;
+    c[u] = q[u] = nt[u] = 0;
+    if (u < nslot && s < a.batch) {
+      const int q0 = a.cu_q[s];
+      q[u] = max(a.cu_q[s + 1] - q0, 0);
+      c[u] = max(a.ctx_lens[s], 0);
+      nt[u] = (q[u] + tpt - 1) >> tpt_shift;
+    }
+  }
+  // first tile of slot u's sequence whose weight is >= x tiles (nt[u] if none)
+  auto first_ge = [&](int u, int x) {
+    const long xk = (long)x << 6;
+    if (nt[u] == 0 || (long)c[u] + q[u] < xk) return nt[u];
+    const int d = (int)(xk > c[u] ? xk - c[u] : 0);
+    const int j0 = ((d + tpt - 1) >> tpt_shift) - 1;
+    return min(max(j0, 0), nt[u] - 1);
+  };
+  auto total_ge = [&](int x) {
+    int n = 0;
+#pragma unroll
+    for (int u = 0; u < kRankSlots; ++u)
+      if (u < nslot) n += nt[u] - first_ge(u, x);
+    return wave_total(n);
+  };
+  if (r >= total_ge(0)) return false;  // more workgroups than items
+  int wmax = 0;
+#pragma unroll
+  for (int u = 0; u < kRankSlots; ++u) wmax = max(wmax, (c[u] + q[u]) >> 6);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) wmax = max(wmax, __shfl_xor(wmax, o));
+  int lo = 0, hi = __builtin_amdgcn_readfirstlane(wmax) + 1;  // total_ge(lo) > r >= total_ge(hi) = 0
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (total_ge(mid) > r) lo = mid;
+    else hi = mid;
+  }
+  // the item weighs exactly lo tiles; it is number k among those, counted in sequence order
+  int k = r - total_ge(lo + 1);
+  bool found = false;
+#pragma unroll
+  for (int u = 0; u < kRankSlots; ++u) {
+    if (u >= nslot || found) continue;
+    const int j0 = first_ge(u, lo);
+    const int ties = first_ge(u, lo + 1) - j0;  // this sequence's items of weight lo: tiles j0 .. j0 + ties - 1
+    const int incl = wave_scan_incl(ties);
+    const int tot = __builtin_amdgcn_readlane(incl, 63);
+    if (k < tot) {
+      const unsigned long long at = __builtin_amdgcn_ballot_w64(incl > k);
+      const int ln = __builtin_ctzll(at);
+      const int before = __builtin_amdgcn_readlane(incl - ties, ln);
+      *seq_out = u * 64 + ln;
+      *tile_out = __builtin_amdgcn_readlane(j0, ln) + (k - before);
+      found = true;
+    } else {
+      k -= tot;
+    }
+  }
+  return found;
+}
 
 // The waves form two groups of four, one wave of each group per SIMD (waves w and w+4 share a
 // SIMD).  Inside every tile period the groups run the same two phases in opposite order: one
@@ -121,10 +216,27 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // index rotated by the tile index, the workgroups of one sequence spread over all XCDs even
   // when the batch size is a multiple of 8 (unrotated, each sequence would sit on one XCD and a
   // batch of unequal lengths would leave most of the chip idle).
-  const int sh = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
-  const int seq = sh / a.n_hgroups, hg = sh - seq * a.n_hgroups;
-  const int tile = a.ntiles_x - 1 - (int)blockIdx.y;
+  int seq, hg, tile, piece;
   const int tpt = COLS >> a.gshift;
+  if (a.ranked) {
+    // linear id -> (item rank, head group, piece): the pieces and head groups of an item are
+    // neighbours in the dispatch order, i.e. they start together and spread over the XCDs
+    const unsigned lid = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned per_item = (unsigned)(a.n_hgroups * a.kv_splits);
+    const int r = (int)(lid / per_item);
+    const int sub = (int)(lid - (unsigned)r * per_item);
+    hg = sub / a.kv_splits;
+    piece = sub - hg * a.kv_splits;
+    if (!ranked_item(a, (SPLIT ? 7 : 8) - a.gshift, r, lane, &seq, &tile)) return;
+    seq = __builtin_amdgcn_readfirstlane(seq);
+    tile = __builtin_amdgcn_readfirstlane(tile);
+  } else {
+    const int sh = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
+    seq = sh / a.n_hgroups;
+    hg = sh - seq * a.n_hgroups;
+    tile = a.ntiles_x - 1 - (int)blockIdx.y;
+    piece = (int)blockIdx.z;
+  }
   const int q0 = a.cu_q[seq];
   const int q_len = a.cu_q[seq + 1] - q0;
   const int tok0 = tile * tpt;
@@ -174,10 +286,10 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   int t_begin = 0, T = T_all;
   if (PART) {
     const int per = (T_all + a.kv_splits - 1) / a.kv_splits;
-    t_begin = (int)blockIdx.z * per;
+    t_begin = piece * per;
     T = min(T_all, t_begin + per);
   }
-  const long prow = ((long)(q0 + token) * a.Hq + head) * a.kv_splits + (PART ? (int)blockIdx.z : 0);  // partial slot
+  const long prow = ((long)(q0 + token) * a.Hq + head) * a.kv_splits + (PART ? piece : 0);  // partial slot
   if (PART && t_begin >= T) {  // nothing left for this piece: an empty partial
     if (valid && half == 0) *reinterpret_cast<f32x2 *>(a.part_ml + prow * 2) = (f32x2){-INFINITY, 0.f};
     return;
@@ -532,6 +644,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 static int g_split_mode = 0;
 static int g_kv_splits = 0;
 static int g_short_chunk_mode = 0;
+static int g_order_mode = 0;
+void set_prefill_order(int mode) { g_order_mode = mode; }
 void set_prefill_short_chunk(int mode) { g_short_chunk_mode = mode; }
 void set_prefill_split(int mode) { g_split_mode = mode; }
 void set_prefill_kv_splits(int n) { g_kv_splits = n; }
@@ -657,6 +771,12 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
     if (kvs < 1) kvs = 1;
   }
   a.kv_splits = kvs;
+  // Heaviest-first dispatch when the static (tile, sequence) order is not already that: several
+  // sequences with cached prefixes (without prefixes the last query tiles of all sequences are
+  // the heaviest items, and they are first in the static order too).
+  a.batch = batch;
+  const bool can_rank = batch <= 64 * kRankSlots;
+  a.ranked = can_rank && (g_order_mode == 0 ? batch >= 2 && max_kv_len > max_q_len : g_order_mode == 2);
   a.part_o = (float *)workspace;
   a.part_ml = a.part_o + (size_t)rows * kvs * c.head_dim;
 

@@ -44,7 +44,8 @@ void set_decode_chunk(int chunk);
 void set_decode_ring(int slots);   // LDS ring depth of the decode split kernel: 0 heuristic, 2..4
 void set_prefill_kv_splits(int n);  // pieces a query tile's key range is cut into: 0 heuristic, 1..16
 void set_prefill_short_chunk(int mode);  // 0 heuristic, 1 short query chunks stay on the prefill kernel
-void set_prefill_split(int mode);  // 0 heuristic, 1 never split the key range over the wave groups, 2 always
+void set_prefill_split(int mode);
+void set_prefill_order(int mode);  // 0 heuristic, 1 workgroups in (tile, sequence) order, 2 heaviest work item first  // 0 heuristic, 1 never split the key range over the wave groups, 2 always
 
 // Log-sum-exp merge of per-split partials: part_o [rows][nsplit][head_dim] fp32 un-normalised,
 // part_ml [rows][nsplit][2] fp32 (max in log2 units, sum); out [rows][head_dim] bf16.

@@ -49,7 +49,7 @@ class GpuRunner:
 
         w, sp = self.w, self.sp
         q = to_dev(st.q)
-        out = torch.empty_like(q)
+        out = torch.full_like(q, float("nan"))   # a row the kernels never write cannot pass by accident
         if st.kind == "prefill":
             need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], int(st.new_lens.max()),
                                                      int(st.seq_lens.max()), w.Hq, w.Hkv, w.d) if self.prefill_workspace else 0
@@ -73,7 +73,7 @@ class GpuRunner:
         w, sp = self.w, self.sp
         assert st.kind == "decode" and (st.new_lens == 1).all()
         q = to_dev(st.q)
-        out = torch.empty_like(q)
+        out = torch.full_like(q, float("nan"))   # a row the kernels never write cannot pass by accident
         mx = int(st.seq_lens.max())
         need = sp.sp_attn_decode_workspace_size(w.batch, mx, w.Hq, w.d)
         if self.ws is None or self.ws.numel() < need:

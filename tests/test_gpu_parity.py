@@ -130,6 +130,50 @@ def test_prefill_key_range_cut_into_pieces(mode, pieces, Hq, Hkv, d):
         sp.sp_debug_set_tuning("prefill_kv_splits", 0)
 
 
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("mode,pieces", [(1, 0), (2, 0), (1, 3), (2, 5)])
+def test_prefill_dispatch_orders(order, mode, pieces):
+    """Work items by launch index (1) and heaviest first (2: every workgroup finds the item of its
+    rank by itself), on ragged chunks over ragged prefixes: sequences without new tokens, without
+    prefix, chunks of one token, equal weights, more than 64 sequences (two per lane)."""
+    import paper_2507_11830_amd as sp
+
+    rng = np.random.default_rng(71)
+    new = np.concatenate([[0, 1, 300, 64, 64, 17, 0, 129], rng.integers(0, 40, 70)])
+    ctx = np.concatenate([[50, 0, 1000, 2048, 2048, 3000, 0, 511], rng.integers(0, 600, 70)])
+    sp.sp_debug_set_tuning("prefill_order", order)
+    sp.sp_debug_set_tuning("prefill_split", mode)
+    sp.sp_debug_set_tuning("prefill_kv_splits", pieces)
+    sp.sp_debug_set_tuning("prefill_short_chunk", 1)
+    try:
+        run_full_compare(custom_workload(f"order-{order}-{mode}-{pieces}", ctx + new, ctx, 8, 1, 128, "prefill", seed=72))
+        run_full_compare(custom_workload(f"order-kv2-{order}-{mode}-{pieces}", (ctx + new)[:9], ctx[:9], 8, 2, 64,
+                                         "prefill", seed=73))
+    finally:
+        for key in ("prefill_order", "prefill_split", "prefill_kv_splits", "prefill_short_chunk"):
+            sp.sp_debug_set_tuning(key, 0)
+
+
+def test_prefill_dispatch_orders_agree_bitwise():
+    """The order in which workgroups pick their items changes nothing in any item's arithmetic."""
+    import paper_2507_11830_amd as sp
+
+    new = np.array([100, 256, 31, 256, 0, 5])
+    ctx = np.array([900, 0, 4000, 256, 77, 1300])
+    outs = []
+    for order in (1, 2):
+        sp.sp_debug_set_tuning("prefill_order", order)
+        try:
+            wl = custom_workload("order-bits", ctx + new, ctx, 8, 1, 128, "prefill", seed=74)
+            g = GpuRunner(wl)
+            for st in wl.steps():
+                g.append(st)
+            outs.append(g.attend(st))
+        finally:
+            sp.sp_debug_set_tuning("prefill_order", 0)
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_prefill_without_workspace_matches_with_workspace():
     """The workspace is optional: without it the same call computes every key range in one piece."""
     w = custom_workload("no-ws", [600, 40, 2100], [580, 0, 2000], 8, 1, 128, "prefill", seed=72)
