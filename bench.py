@@ -398,11 +398,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the ceiling kernels and the C5a / C5c / C4 / C5b side measurements")
-    ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5c", "spec", "copy"],
-                    help="main = the step described above; c5a / c5c / spec = only that side workload "
+    ap.add_argument("--workload", default="main", choices=["main", "c5a", "c5b", "c5c", "spec", "copy"],
+                    help="main = the step described above; c5a / c5b / c5c / spec = only that side workload "
                          "(used for per-kernel profiles); copy = a plain 1 GiB device copy, the "
                          "known-size kernel the HBM byte counters are calibrated against")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="sp_debug_set_tuning override for this run (profiling of non-default launch shapes)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs one GPU's head shard only (no collectives, no sharding); "
@@ -417,6 +419,9 @@ def main():
     import workloads as W
 
     sp.lib()   # fail loudly if the HIP library is missing
+    for kv in args.tune:
+        key, _, value = kv.partition("=")
+        sp.sp_debug_set_tuning(key, int(value))
     if args.workload == "copy":
         n = 1 << 30
         src = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
@@ -426,6 +431,9 @@ def main():
                           "GBps_read_plus_write": 2 * n / per[0] / 1e6}))
         return
     if args.workload != "main":
+        if args.workload == "c5b":
+            print(json.dumps(extra_shift_decode(sp, steps=args.steps)))
+            return
         fn = {"c5a": extra_long_prefill, "c5c": extra_big_decode, "spec": extra_spec_verify}[args.workload]
         print(json.dumps(fn(sp, iters=args.steps)))
         return

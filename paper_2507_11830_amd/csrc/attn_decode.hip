@@ -389,137 +389,121 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
 __device__ __forceinline__ float lane_bcast(float x, int k) {
   return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), k));
 }
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-  return x;
+// Wave-wide max, returned wave-uniform: running max inside rows of 16 lanes by DPP shifts, then
+// the two row broadcasts (gfx9 DPP), so that lane 63 holds the result.  Lanes without a source
+// lane keep their own value.
+template <int CTRL, int ROWS>
+__device__ __forceinline__ float dpp_or_self(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(__float_as_uint(x), __float_as_uint(x), CTRL, ROWS, 0xF, false));
 }
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-  return x;
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp_or_self<0x111, 0xF>(x));  // row_shr:1
+  x = fmaxf(x, dpp_or_self<0x112, 0xF>(x));  // row_shr:2
+  x = fmaxf(x, dpp_or_self<0x114, 0xF>(x));  // row_shr:4
+  x = fmaxf(x, dpp_or_self<0x118, 0xF>(x));  // row_shr:8
+  x = fmaxf(x, dpp_or_self<0x142, 0xA>(x));  // row_bcast:15 into rows 1 and 3
+  x = fmaxf(x, dpp_or_self<0x143, 0xC>(x));  // row_bcast:31 into rows 2 and 3
+  return lane_bcast(x, 63);
 }
 
-// One workgroup of W waves per output row (a (sequence, head) of a decode batch, or a
-// (token, head) of a key-split prefill).  Every split of the row holds a partial, real or
-// empty (m = -inf), so nothing depends on sequence lengths: the (m, l) pairs and the first few
-// partial rows are requested in one memory round trip.  Wave w reduces the contiguous range of
-// splits [w * per, (w + 1) * per): lane k holds the weight of the range's k-th split (64 per
-// round), every lane owns two output channels and accumulates splits in index order; the W
-// running states are then merged in wave order, so the result does not depend on timing.
-// A row with no keys at all (every m = -inf) is written as zeros.
-template <int D, int W>
-__global__ __launch_bounds__(64 * W) void combine_kernel(const float *__restrict__ part_o,
-                                                         const float *__restrict__ part_ml,
-                                                         char *__restrict__ out, int nsplit) {
-  constexpr int SPEC = 8;  // partial rows fetched before their weights are known
-  const int row = blockIdx.x;
-  const int lane = threadIdx.x & 63;
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int ch = (lane % (D / 2)) * 2;
-  const bool writer = threadIdx.x < D / 2;
-  bf16x2 *dst = reinterpret_cast<bf16x2 *>(out + ((long)row * D + ch) * 2);
+// One wave per 32-channel slice of an output row (a (sequence, head) of a decode batch, or a
+// (token, head) of a key-split prefill).  The kernel is nothing but a chain of memory round trips,
+// so it is built to be one trip long and to spread over many CUs: eight lanes x 16 bytes cover the
+// slice of one split, a load instruction therefore covers eight splits, and NB of them (up to 256
+// splits; NB is picked by the host from the split count) plus the matching (m, l) pairs are
+// requested before any weight is known.  The loads are unconditional (indices past the end are
+// clamped and their weights forced to 0): behind a branch each would wait for the one before.  Every split of
+// the row holds a partial, real or empty (m = -inf; its o holds stale bytes that are only ever
+// selected away, never multiplied by 0), so nothing depends on sequence lengths.  Lane group g
+// accumulates the splits g, g + 8, g + 16, ... in that order and the eight groups are then added in
+// a fixed butterfly, so the result does not depend on timing.  A row with no keys at all (every
+// m = -inf) is written as zeros.
+template <int D, int NB>
+__global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ part_o,
+                                                     const float *__restrict__ part_ml,
+                                                     char *__restrict__ out, int nsplit) {
+  constexpr int SL = D / 32;  // slices per row
+  const long row = blockIdx.x / SL;
+  const int sl = (int)(blockIdx.x - row * SL);
+  const int lane = threadIdx.x;
+  const int g = lane >> 3, ch = sl * 32 + (lane & 7) * 4;
+  bf16x4 *dst = reinterpret_cast<bf16x4 *>(out + (row * D + ch) * 2);
   if (part_o == nullptr) {  // every sequence of the batch is empty
-    if (writer) *dst = __builtin_convertvector((f32x2){0.f, 0.f}, bf16x2);
+    if (g == 0) *dst = __builtin_convertvector((f32x4){0.f, 0.f, 0.f, 0.f}, bf16x4);
     return;
   }
-  const int per = (nsplit + W - 1) / W;
-  const int k0 = min(w * per, nsplit), k1 = min(nsplit, k0 + per);
-  const f32x2 *ml = reinterpret_cast<const f32x2 *>(part_ml) + (long)row * nsplit;
-  const float *po = part_o + (long)row * nsplit * D + ch;
-  f32x2 spec[SPEC];  // empty splits hold stale bytes here: only ever selected, never multiplied by 0
+  const f32x2 *ml = reinterpret_cast<const f32x2 *>(part_ml) + row * nsplit;
+  const float *po = part_o + row * nsplit * D + ch;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float den = 0.f, M = -INFINITY;
+  for (int base = 0; base < nsplit; base += 8 * NB) {
+    f32x2 w[NB];
+    f32x4 v[NB];
 #pragma unroll
-  for (int u = 0; u < SPEC; ++u) spec[u] = *reinterpret_cast<const f32x2 *>(po + (long)min(k0 + u, nsplit - 1) * D);
-  float M = -INFINITY;
-  for (int k = k0 + lane; k < k1; k += 64) M = fmaxf(M, ml[k][0]);
-  M = wave_max(M);
-  float a0 = 0.f, a1 = 0.f, den = 0.f;
-  if (M != -INFINITY) {
-    for (int base = k0; base < k1; base += 64) {
-      const int cnt = min(64, k1 - base);
-      float f = 0.f;
-      if (lane < cnt) {
-        f32x2 v = ml[base + lane];
-        f = __builtin_amdgcn_exp2f(v[0] - M);  // 0 for an empty split
-        den += f * v[1];
-      }
-      int k = 0;
-      if (base == k0) {
-#pragma unroll
-        for (int u = 0; u < SPEC; ++u) {
-          float fu = u < cnt ? lane_bcast(f, u) : 0.f;
-          a0 += fu != 0.f ? fu * spec[u][0] : 0.f;
-          a1 += fu != 0.f ? fu * spec[u][1] : 0.f;
-        }
-        k = SPEC;
-      }
-      for (; k < cnt; k += 16) {  // sixteen independent loads in flight per lane; the last batch is padded
-        f32x2 v[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = *reinterpret_cast<const f32x2 *>(po + (long)(base + min(k + u, cnt - 1)) * D);
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          float fu = k + u < cnt ? lane_bcast(f, min(k + u, 63)) : 0.f;
-          a0 += fu != 0.f ? fu * v[u][0] : 0.f;
-          a1 += fu != 0.f ? fu * v[u][1] : 0.f;
-        }
-      }
+    for (int u = 0; u < NB; ++u) {
+      const int sc = min(base + 8 * u + g, nsplit - 1);  // past the end: the last split again, weight forced to 0
+      w[u] = ml[sc];
+      v[u] = *reinterpret_cast<const f32x4 *>(po + (long)sc * D);
     }
-    den = wave_sum(den);
-  }
-  if (W > 1) {
-    __shared__ float s_m[W], s_den[W], s_a[W][64][2];
-    if (lane == 0) {
-      s_m[w] = M;
-      s_den[w] = den;
-    }
-    s_a[w][lane][0] = a0;
-    s_a[w][lane][1] = a1;
-    __syncthreads();
-    if (w != 0) return;
-    float Mg = s_m[0];
+    // Everything above is in flight before anything below waits for it; the code below has no
+    // branches either (given one, the compiler moves the row loads behind it, i.e. behind the wait
+    // for the (m, l) pairs: a second round trip).
+    __builtin_amdgcn_sched_barrier(0);
+    float mb = -INFINITY;
 #pragma unroll
-    for (int i = 1; i < W; ++i) Mg = fmaxf(Mg, s_m[i]);
-    M = Mg;
-    a0 = a1 = den = 0.f;
-    if (Mg != -INFINITY) {
+    for (int u = 0; u < NB; ++u) mb = fmaxf(mb, base + 8 * u + g < nsplit ? w[u][0] : -INFINITY);
+    const float Mn = fmaxf(M, wave_max(mb));                               // still -inf: only empty splits so far
+    const float alpha = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - Mn);  // rescale of what has been accumulated
+    acc *= alpha;
+    den *= alpha;
+    M = Mn;
 #pragma unroll
-      for (int i = 0; i < W; ++i) {
-        const float f = __builtin_amdgcn_exp2f(s_m[i] - Mg);  // 0 for a wave whose range was empty
-        if (f != 0.f) {
-          den += f * s_den[i];
-          a0 += f * s_a[i][lane][0];
-          a1 += f * s_a[i][lane][1];
-        }
-      }
+    for (int u = 0; u < NB; ++u) {
+      const bool live = base + 8 * u + g < nsplit && w[u][0] != -INFINITY;  // not past the end, not an empty split
+      const float f = live ? __builtin_amdgcn_exp2f(w[u][0] - M) : 0.f;
+      den += live ? f * w[u][1] : 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] += live ? f * v[u][j] : 0.f;
     }
   }
+  // the eight lane groups hold disjoint sets of splits of the same channels
+#pragma unroll
+  for (int o = 8; o <= 32; o <<= 1) {
+    den += __shfl_xor(den, o);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] += __shfl_xor(acc[j], o);
+  }
+  if (g != 0) return;
   if (M == -INFINITY) {
-    if (writer) *dst = __builtin_convertvector((f32x2){0.f, 0.f}, bf16x2);
+    *dst = __builtin_convertvector((f32x4){0.f, 0.f, 0.f, 0.f}, bf16x4);
     return;
   }
-  float inv = 1.0f / den;
-  if (writer) *dst = __builtin_convertvector((f32x2){a0 * inv, a1 * inv}, bf16x2);
+  const float inv = 1.0f / den;
+  *dst = __builtin_convertvector(acc * inv, bf16x4);
 }
 
 int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
                    hipStream_t stream) {
   if (rows <= 0) return SP_OK;
-  if (rows > 0x7fffffffL) return fail(SP_ERR_BAD_SHAPE, "combine: %ld rows exceed the grid limit", rows);
-  // many splits per row: several waves share the row (each wave's loop is a chain of dependent
-  // memory round trips, one per eight splits)
-  const int waves = nsplit > 128 ? 8 : nsplit > 32 ? 4 : 1;
-  const dim3 grid((unsigned)rows);
+  const long blocks = rows * (head_dim / 32);
+  if (blocks > 0x7fffffffL) return fail(SP_ERR_BAD_SHAPE, "combine: %ld rows exceed the grid limit", rows);
+  const dim3 grid((unsigned)blocks);
   char *o = (char *)out;
+  const int nb = nsplit <= 32 ? 4 : nsplit <= 64 ? 8 : nsplit <= 128 ? 16 : 32;  // >= ceil(nsplit / 8) up to 256 splits
+#define SP_COMBINE(D_, NB_) \
+  hipLaunchKernelGGL((combine_kernel<D_, NB_>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit)
   if (head_dim == 128) {
-    if (waves == 8) hipLaunchKernelGGL((combine_kernel<128, 8>), grid, dim3(512), 0, stream, part_o, part_ml, o, nsplit);
-    else if (waves == 4) hipLaunchKernelGGL((combine_kernel<128, 4>), grid, dim3(256), 0, stream, part_o, part_ml, o, nsplit);
-    else hipLaunchKernelGGL((combine_kernel<128, 1>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit);
+    if (nb == 4) SP_COMBINE(128, 4);
+    else if (nb == 8) SP_COMBINE(128, 8);
+    else if (nb == 16) SP_COMBINE(128, 16);
+    else SP_COMBINE(128, 32);
   } else {
-    if (waves == 8) hipLaunchKernelGGL((combine_kernel<64, 8>), grid, dim3(512), 0, stream, part_o, part_ml, o, nsplit);
-    else if (waves == 4) hipLaunchKernelGGL((combine_kernel<64, 4>), grid, dim3(256), 0, stream, part_o, part_ml, o, nsplit);
-    else hipLaunchKernelGGL((combine_kernel<64, 1>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit);
+    if (nb == 4) SP_COMBINE(64, 4);
+    else if (nb == 8) SP_COMBINE(64, 8);
+    else if (nb == 16) SP_COMBINE(64, 16);
+    else SP_COMBINE(64, 32);
   }
+#undef SP_COMBINE
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "combine launch: %s", hipGetErrorString(e));
   return SP_OK;
