@@ -13,8 +13,8 @@
 // kernel is latency-bound unless every CU has several blocks outstanding at all times, and
 // LDS (160 KiB per CU) holds far more in-flight data than registers can; nothing in the loop
 // synchronises with another wave.  Each wave writes one un-normalised fp32 partial (o, m, l)
-// per head.  Combine kernel: out = sum_k 2^(m_k - M) o_k / sum_k 2^(m_k - M) l_k in fixed
-// split order, one round-to-nearest-even to bf16.
+// per head.  Combine kernel: out = sum_k 2^(m_k - M) o_k / sum_k 2^(m_k - M) l_k in a fixed
+// summation order, one round-to-nearest-even to bf16.
 //
 // Bound: HBM bandwidth.  Algorithmic bytes: 4 * head_dim per cached token per KV head.
 #include "attn_tile.h"

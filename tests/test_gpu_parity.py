@@ -229,10 +229,11 @@ def test_fused_decode_step_c3_full():
     run_fused_steps(W.c3_decode())
 
 
-@pytest.mark.parametrize("length", [5000, 20000])
+@pytest.mark.parametrize("length", [5000, 12000, 20000])
 def test_decode_single_long_sequence_many_splits(length):
-    """One long sequence: 40 resp. 157 splits per row, so the combine pass runs its four- resp.
-    eight-wave form."""
+    """One long sequence: 40, 94 resp. 157 splits per row, so the combine pass runs its forms with
+    8, 16 resp. 32 load instructions per batch (the 4-instruction form serves every short case, the
+    100 000-token test several batches)."""
     lens = np.array([length])
     run_full_compare(custom_workload(f"decode-long-{length}", lens, lens - 1, 8, 1, 128, "decode", seed=73), check_cache=False)
 
