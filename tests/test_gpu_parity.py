@@ -154,6 +154,17 @@ def test_prefill_dispatch_orders(order, mode, pieces):
             sp.sp_debug_set_tuning(key, 0)
 
 
+@pytest.mark.parametrize("batch", [256, 257])
+def test_prefill_heaviest_first_at_its_batch_limit(batch):
+    """256 sequences fill every lane slot of the in-kernel ranking; one more and the launch goes
+    back to the static order."""
+    rng = np.random.default_rng(75)
+    new = rng.integers(0, 20, batch)
+    ctx = rng.integers(0, 200, batch)
+    new[rng.integers(0, batch)] = 150
+    run_full_compare(custom_workload(f"rank-limit-{batch}", ctx + new, ctx, 4, 1, 128, "prefill", seed=76))
+
+
 def test_prefill_dispatch_orders_agree_bitwise():
     """The order in which workgroups pick their items changes nothing in any item's arithmetic."""
     import paper_2507_11830_amd as sp
