@@ -596,6 +596,10 @@ def test_random_shapes_against_oracle(seed):
     ctx = np.minimum(ctx, np.maximum(total - 1, 0))
     print(f"[shape] seed {seed}: Hq {Hkv * G} Hkv {Hkv} d {d} total {total.tolist()} ctx {ctx.tolist()}", flush=True)
     run_full_compare(custom_workload(f"rand-p-{seed}", total, ctx, Hkv * G, Hkv, d, "prefill", seed=2000 + seed))
+    # the same sequences with a chunk of at most 32 / G tokens each: the short-chunk path
+    short = np.minimum(rng.integers(0, max(32 // min(G, 32), 1) + 1, size=B), total)
+    if short.max() > 0:
+        run_full_compare(custom_workload(f"rand-s-{seed}", total, total - short, Hkv * G, Hkv, d, "prefill", seed=5000 + seed))
     dec = np.where(total > 0, total, 1)
     run_full_compare(custom_workload(f"rand-d-{seed}", dec, dec - 1, Hkv * G, Hkv, d, "decode", seed=3000 + seed))
     run_fused_steps(custom_workload(f"rand-f-{seed}", dec, dec - 1, Hkv * G, Hkv, d, "decode", seed=4000 + seed))
