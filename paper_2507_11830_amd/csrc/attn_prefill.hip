@@ -61,7 +61,8 @@ struct PrefillArgs {
   float *part_o, *part_ml;
   int kv_splits;
   int batch;
-  int ranked;  // workgroups take their work items heaviest first (ranked_item below)
+  int ranked;      // workgroups take their work items heaviest first (ranked_item below)
+  int rank_shift;  // log2 of the weight unit in keys
 };
 
 // Inclusive prefix sum over the 64 lanes (gfx9 DPP: shifts inside rows of 16, then the two row
@@ -76,6 +77,17 @@ __device__ __forceinline__ int wave_scan_incl(int x) {
   return x;
 }
 __device__ __forceinline__ int wave_total(int x) { return __builtin_amdgcn_readlane(wave_scan_incl(x), 63); }
+// Wave-wide max of non-negative values, wave-uniform (same DPP steps; a lane without a source lane
+// contributes 0).
+__device__ __forceinline__ int wave_max_i(int x) {
+  x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, false));
+  x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, false));
+  x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, false));
+  x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, false));
+  x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false));
+  x = max(x, __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false));
+  return __builtin_amdgcn_readlane(x, 63);
+}
 
 // Ranked dispatch.  The hardware starts workgroups in linear id order and a CU takes the next one
 // when it has room, so the launch is a list schedule and its makespan depends on the list's
@@ -83,34 +95,44 @@ __device__ __forceinline__ int wave_total(int x) { return __builtin_amdgcn_readl
 // sit on cached prefixes of very different lengths is far from it in (tile, sequence) order (the
 // early query tiles of the sequence with the longest prefix are as heavy as anything in the batch
 // but would start last).  Here the workgroup with linear id r finds the r-th heaviest (sequence,
-// query tile) item by itself: the weight of an item is its number of visible keys in 64-key
-// tiles, the number of items at least as heavy as x is a sum over sequences of a closed form, so
-// a binary search over x and one prefix sum over the ties select the item in a few hundred
-// instructions, from the same two length arrays every workgroup reads anyway.  One sequence per
-// lane and slot: batches of up to 64 * kRankSlots sequences.
+// query tile) item by itself: the weight of an item is its number of visible keys in units of
+// 2^rank_shift keys (the host picks the unit so that the heaviest item weighs at most 63: finer
+// classes would not change the makespan, and every doubling costs a probe), the number of items at
+// least as heavy as x is a sum over sequences of a closed form, so a binary search over x and one
+// prefix sum over the ties select the item in a few hundred instructions, from the same two
+// length arrays every workgroup reads anyway.  Ties are taken sequence by sequence, later tiles first.  One
+// sequence per lane and slot: batches of up to 64 * kRankSlots sequences.  The search is a chain
+// of dependent cross-lane operations in a single wave (about 0.2 us per probe), which is why the
+// probes are few and DPP, not LDS permutes, carries them.
 constexpr int kRankSlots = 4;
 
-__device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift, int r, int lane, int *seq_out,
-                                            int *tile_out) {
+struct RankedItem {
+  int seq, tile;
+  int q0, q_len, ctx;  // the sequence's entries of the length arrays, so that nobody has to load them again
+};
+
+__device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift, int r, int lane, RankedItem *out) {
   const int tpt = 1 << tpt_shift;
-  int c[kRankSlots], q[kRankSlots], nt[kRankSlots];
+  int c[kRankSlots], q[kRankSlots], nt[kRankSlots], qs[kRankSlots];
   const int nslot = (a.batch + 63) >> 6;  // uniform
 #pragma unroll
   for (int u = 0; u < kRankSlots; ++u) {
     const int s = u * 64 + lane;
-    c[u] = q[u] = nt[u] = 0;
+    c[u] = q[u] = nt[u] = qs[u] = 0;
     if (u < nslot && s < a.batch) {
       const int q0 = a.cu_q[s];
+      qs[u] = q0;
       q[u] = max(a.cu_q[s + 1] - q0, 0);
       c[u] = max(a.ctx_lens[s], 0);
       nt[u] = (q[u] + tpt - 1) >> tpt_shift;
     }
   }
-  // first tile of slot u's sequence whose weight is >= x tiles (nt[u] if none)
+  const int wsh = a.rank_shift;
+  // first tile of slot u's sequence whose weight is >= x units (nt[u] if none)
   auto first_ge = [&](int u, int x) {
-    const long xk = (long)x << 6;
-    if (nt[u] == 0 || (long)c[u] + q[u] < xk) return nt[u];
-    const int d = (int)(xk > c[u] ? xk - c[u] : 0);
+    const int xk = x << wsh;  // keys; x never exceeds the heaviest item's weight + 1
+    if (nt[u] == 0 || c[u] + q[u] < xk) return nt[u];
+    const int d = max(xk - c[u], 0);
     const int j0 = ((d + tpt - 1) >> tpt_shift) - 1;
     return min(max(j0, 0), nt[u] - 1);
   };
@@ -121,20 +143,27 @@ __device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift,
       if (u < nslot) n += nt[u] - first_ge(u, x);
     return wave_total(n);
   };
-  if (r >= total_ge(0)) return false;  // more workgroups than items
-  int wmax = 0;
+  int n_items = 0, wmax = 0;
 #pragma unroll
-  for (int u = 0; u < kRankSlots; ++u) wmax = max(wmax, (c[u] + q[u]) >> 6);
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) wmax = max(wmax, __shfl_xor(wmax, o));
-  int lo = 0, hi = __builtin_amdgcn_readfirstlane(wmax) + 1;  // total_ge(lo) > r >= total_ge(hi) = 0
+  for (int u = 0; u < kRankSlots; ++u) {
+    n_items += nt[u];
+    wmax = max(wmax, nt[u] ? (c[u] + q[u]) >> wsh : 0);
+  }
+  if (r >= wave_total(n_items)) return false;  // more workgroups than items
+  wmax = wave_max_i(wmax);
+  int lo = 0, hi = wmax + 1, n_hi = 0;  // total_ge(lo) > r >= total_ge(hi) = n_hi
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
-    if (total_ge(mid) > r) lo = mid;
-    else hi = mid;
+    const int n = total_ge(mid);
+    if (n > r) {
+      lo = mid;
+    } else {
+      hi = mid;
+      n_hi = n;
+    }
   }
-  // the item weighs exactly lo tiles; it is number k among those, counted in sequence order
-  int k = r - total_ge(lo + 1);
+  // the item weighs exactly lo units; it is number k among those, counted in sequence order
+  int k = r - n_hi;
   bool found = false;
 #pragma unroll
   for (int u = 0; u < kRankSlots; ++u) {
@@ -147,8 +176,12 @@ __device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift,
       const unsigned long long at = __builtin_amdgcn_ballot_w64(incl > k);
       const int ln = __builtin_ctzll(at);
       const int before = __builtin_amdgcn_readlane(incl - ties, ln);
-      *seq_out = u * 64 + ln;
-      *tile_out = __builtin_amdgcn_readlane(j0, ln) + (k - before);
+      out->seq = u * 64 + ln;
+      const int t_ln = __builtin_amdgcn_readlane(ties, ln);
+      out->tile = __builtin_amdgcn_readlane(j0, ln) + (t_ln - 1 - (k - before));  // the sequence's later (heavier) tiles first
+      out->q0 = __builtin_amdgcn_readlane(qs[u], ln);
+      out->q_len = __builtin_amdgcn_readlane(q[u], ln);
+      out->ctx = __builtin_amdgcn_readlane(c[u], ln);
       found = true;
     } else {
       k -= tot;
@@ -216,7 +249,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // index rotated by the tile index, the workgroups of one sequence spread over all XCDs even
   // when the batch size is a multiple of 8 (unrotated, each sequence would sit on one XCD and a
   // batch of unequal lengths would leave most of the chip idle).
-  int seq, hg, tile, piece;
+  int seq, hg, tile, piece, q0, q_len, ctx;
   const int tpt = COLS >> a.gshift;
   if (a.ranked) {
     // linear id -> (item rank, head group, piece): the pieces and head groups of an item are
@@ -227,21 +260,25 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     const int sub = (int)(lid - (unsigned)r * per_item);
     hg = sub / a.kv_splits;
     piece = sub - hg * a.kv_splits;
-    if (!ranked_item(a, (SPLIT ? 7 : 8) - a.gshift, r, lane, &seq, &tile)) return;
-    seq = __builtin_amdgcn_readfirstlane(seq);
-    tile = __builtin_amdgcn_readfirstlane(tile);
+    RankedItem it;
+    if (!ranked_item(a, (SPLIT ? 7 : 8) - a.gshift, r, lane, &it)) return;
+    seq = __builtin_amdgcn_readfirstlane(it.seq);
+    tile = __builtin_amdgcn_readfirstlane(it.tile);
+    q0 = __builtin_amdgcn_readfirstlane(it.q0);
+    q_len = __builtin_amdgcn_readfirstlane(it.q_len);
+    ctx = __builtin_amdgcn_readfirstlane(it.ctx);
   } else {
     const int sh = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
     seq = sh / a.n_hgroups;
     hg = sh - seq * a.n_hgroups;
     tile = a.ntiles_x - 1 - (int)blockIdx.y;
     piece = (int)blockIdx.z;
+    q0 = a.cu_q[seq];
+    q_len = a.cu_q[seq + 1] - q0;
+    ctx = a.ctx_lens[seq];
   }
-  const int q0 = a.cu_q[seq];
-  const int q_len = a.cu_q[seq + 1] - q0;
   const int tok0 = tile * tpt;
   if (tok0 >= q_len) return;
-  const int ctx = a.ctx_lens[seq];
   const int kv_end = ctx + min(q_len, tok0 + tpt);
   const int kvh = (hg << a.gshift) / (a.Hq / a.Hkv);
   const int32_t *bt_row = a.block_table + (long)seq * a.max_pages;
@@ -777,6 +814,8 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   a.batch = batch;
   const bool can_rank = batch <= 64 * kRankSlots;
   a.ranked = can_rank && (g_order_mode == 0 ? batch >= 2 && max_kv_len > max_q_len : g_order_mode == 2);
+  a.rank_shift = 6;
+  while (a.rank_shift < 24 && (max_kv_len >> a.rank_shift) > 63) ++a.rank_shift;
   a.part_o = (float *)workspace;
   a.part_ml = a.part_o + (size_t)rows * kvs * c.head_dim;
 
