@@ -184,7 +184,8 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a power of two in
  *                   [128, 1024].  Changes what sp_attn_decode_workspace_size returns.
  *   "decode_ring"   32-key blocks a decode wave keeps in its LDS ring (one computed on, the
- *                   rest in flight): 0 (built-in choice) or 2..4.
+ *                   rest in flight): 0 (built-in choice), 2..4, or 1 for two K blocks and a
+ *                   single V block (less LDS per wave, one more resident wave per CU).
  *   "prefill_kv_splits" pieces the key range of a prefill query tile is cut into when a
  *                   workspace is given: 0 (built-in heuristic) or 1..16 (still bounded by the
  *                   workspace size).

@@ -202,8 +202,7 @@ int sp_debug_set_tuning(const char *key, int32_t value) {
     return SP_OK;
   }
   if (!strcmp(key, "decode_ring")) {
-    if (value != 0 && (value < 2 || value > 4))
-      return fail(SP_ERR_UNSUPPORTED, "decode_ring=%d (0, or 2..4)", value);
+    if (value < 0 || value > 4) return fail(SP_ERR_UNSUPPORTED, "decode_ring=%d (0..4)", value);
     set_decode_ring(value);
     return SP_OK;
   }

@@ -108,6 +108,12 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   constexpr int NI = MBYTES / 1024;     // 1 KiB load instructions per matrix and block
   constexpr int RPI = 1024 / ROWB;      // key rows per load instruction
   constexpr int LPB = 2 * NI;           // load instructions per block
+  // NB = 1 is the "one and a half slot" form: two K blocks but a single V block in LDS (24 KiB
+  // at head_dim 128 instead of 32; LDS is granted in 1280-byte granules, so that is six resident
+  // waves per CU instead of four).  Measured: no faster, the kernel is bandwidth-bound either way.  V of block
+  // i + 1 is requested right after the last read of V of block i and has the next block's
+  // K Q^T and softmax to land.
+  constexpr bool VS = NB == 1;
   static_assert((NB - 1) * LPB < 64, "outstanding loads must fit the vmcnt counter");
   extern __shared__ __align__(16) char smem_raw[];
   lds_char *smem = (lds_char *)smem_raw;
@@ -203,41 +209,46 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   }
   const size_t page_stride = (size_t)a.Hkv * (kPage * ROWB);
   const char *kpool = a.k_pages + (size_t)kvh * (kPage * ROWB), *vpool = a.v_pages + (size_t)kvh * (kPage * ROWB);
-  auto issue_block = [&](int bi) {
-    const unsigned slot_base = (unsigned)((bi % NB) * SLOT);
+  // K (isv = false) or V block bi of the wave's range into the LDS bytes [dst0, dst0 + MBYTES).
+  // The "memory" clobber keeps LDS reads of the bytes being replaced on the near side of the request.
+  auto issue_mat = [&](int bi, bool isv, unsigned dst0) {
+    const char *pool = isv ? vpool : kpool;
     if (32 * bi + 31 <= last_row) {
       // both pages of the block lie inside the range: two page bases, precomputed lane offsets
 #pragma unroll
       for (int pp = 0; pp < 2; ++pp) {
-        const size_t poff = (size_t)(unsigned)__builtin_amdgcn_readlane(my_page, 2 * bi + pp) * page_stride;
-        const char *pbk = kpool + poff, *pbv = vpool + poff;
+        const char *pb = pool + (size_t)(unsigned)__builtin_amdgcn_readlane(my_page, 2 * bi + pp) * page_stride;
 #pragma unroll
         for (int jj = 0; jj < IPP; ++jj) {
-          const unsigned dk = slot_base + (pp * IPP + jj) * 1024, dv = dk + MBYTES;
-          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dk), "v"(voff_k[jj]), "s"(pbk));
-          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dv), "v"(voff_v[jj]), "s"(pbv));
+          const unsigned dst = dst0 + (pp * IPP + jj) * 1024;
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dst),
+                       "v"(isv ? voff_v[jj] : voff_k[jj]), "s"(pb)
+                       : "memory");
         }
       }
       return;
     }
     // the last, partial block: rows past the end are redirected to the last row
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-#pragma unroll
-      for (int j = 0; j < NI; ++j) {
-        const int row0 = 32 * bi + RPI * j;                   // first row of the instruction, relative to kv0
-        const int pslot = min(row0, last_row) >> 4;           // uniform
-        const int rip_lim = pslot == (last_row >> 4) ? (last_row & 15) : 15;
-        const char *pb = (m ? vpool : kpool) + (size_t)(unsigned)__builtin_amdgcn_readlane(my_page, pslot) * page_stride;
-        const int line = 4 * j + dq;                          // line inside the block
-        const int cl = dslot ^ (m ? Z::gv(line) : Z::gk(line));
-        const int rip = (D == 128 ? line : 2 * line + (cl >> 3)) & 15;
-        const int chunk16 = D == 128 ? cl : (cl & 7);
-        const unsigned voff = (unsigned)(min(rip, rip_lim) * ROWB + chunk16 * 16);
-        const unsigned dst = slot_base + m * MBYTES + j * 1024;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dst), "v"(voff), "s"(pb));
-      }
+    for (int j = 0; j < NI; ++j) {
+      const int row0 = 32 * bi + RPI * j;                   // first row of the instruction, relative to kv0
+      const int pslot = min(row0, last_row) >> 4;           // uniform
+      const int rip_lim = pslot == (last_row >> 4) ? (last_row & 15) : 15;
+      const char *pb = pool + (size_t)(unsigned)__builtin_amdgcn_readlane(my_page, pslot) * page_stride;
+      const int line = 4 * j + dq;                          // line inside the block
+      const int cl = dslot ^ (isv ? Z::gv(line) : Z::gk(line));
+      const int rip = (D == 128 ? line : 2 * line + (cl >> 3)) & 15;
+      const int chunk16 = D == 128 ? cl : (cl & 7);
+      const unsigned voff = (unsigned)(min(rip, rip_lim) * ROWB + chunk16 * 16);
+      const unsigned dst = dst0 + j * 1024;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(dst), "v"(voff), "s"(pb)
+                   : "memory");
     }
+  };
+  auto issue_block = [&](int bi) {  // ring forms: K and V of block bi into slot bi % NB
+    const unsigned slot_base = (unsigned)((bi % NB) * SLOT);
+    issue_mat(bi, false, slot_base);
+    issue_mat(bi, true, slot_base + MBYTES);
   };
 
   // ---- LDS operand offsets of this lane inside a slot
@@ -248,7 +259,7 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     const int n = lane & 15, dg = (lane >> 4) & 1;
 #pragma unroll
     for (int db = 0; db < G::kDBlocks; ++db)
-      vofs[db] = MBYTES + Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) + 8 * (n & 1);
+      vofs[db] = Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) + 8 * (n & 1);
   }
   f32x16 o[G::kDBlocks];
 #pragma unroll
@@ -259,18 +270,36 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   // finite floor keeps exp2(m - m) defined for it (the partial is written as empty if l stays 0).
   float m = MQ ? -1e30f : -INFINITY, l = 0.f;
 
+  if (VS) {  // requests are made in the order K0 V0 K1 | V1 K2 | V2 K3 | ... and retire in that order
+    issue_mat(0, false, 0);
+    issue_mat(0, true, 2 * MBYTES);
+    if (nb > 1) issue_mat(1, false, MBYTES);
+  } else {
 #pragma unroll
-  for (int bi = 0; bi < NB - 1; ++bi)
-    if (bi < nb) issue_block(bi);
+    for (int bi = 0; bi < NB - 1; ++bi)
+      if (bi < nb) issue_block(bi);
+  }
   for (int i = 0; i < nb; ++i) {
-    // the slot of block i-1 is free again: keep NB-1 blocks in flight behind block i
-    if (i + NB - 1 < nb) issue_block(i + NB - 1);
-    const int behind = min(NB - 1, nb - 1 - i);  // blocks requested after block i
-    if (behind >= 3 && NB > 3) wait_vmcnt<(NB > 3 ? 3 : 0) * LPB>();
-    else if (behind == 2 && NB > 2) wait_vmcnt<(NB > 2 ? 2 : 0) * LPB>();
-    else if (behind == 1 && NB > 1) wait_vmcnt<(NB > 1 ? 1 : 0) * LPB>();
-    else wait_vmcnt<0>();
-    const lds_char *sb = smem + (i % NB) * SLOT;
+    const lds_char *sbk, *sbv;  // K and V block of this iteration
+    if (VS) {
+      sbk = smem + (i & 1) * MBYTES;
+      sbv = smem + 2 * MBYTES;
+      // behind K(i) in the queue: V(i), and K(i+1) if there is one.  The last block waits for
+      // everything (the fused append patches both of its matrices).
+      if (i + 1 < nb) wait_vmcnt<2 * NI>();
+      else if (APPEND) wait_vmcnt<0>();
+      else wait_vmcnt<NI>();
+    } else {
+      // the slot of block i-1 is free again: keep NB-1 blocks in flight behind block i
+      if (i + NB - 1 < nb) issue_block(i + NB - 1);
+      const int behind = min(NB - 1, nb - 1 - i);  // blocks requested after block i
+      if (behind >= 3 && NB > 3) wait_vmcnt<(NB > 3 ? 3 : 0) * LPB>();
+      else if (behind == 2 && NB > 2) wait_vmcnt<(NB > 2 ? 2 : 0) * LPB>();
+      else if (behind == 1 && NB > 1) wait_vmcnt<(NB > 1 ? 1 : 0) * LPB>();
+      else wait_vmcnt<0>();
+      sbk = smem + (i % NB) * SLOT;
+      sbv = sbk + MBYTES;
+    }
     const int base = kv0 + 32 * i;
     if (APPEND && kv1 == L && i == nb - 1) {
       // The block that holds position L-1 has landed (it is the last one: nothing behind it).
@@ -282,8 +311,8 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
       for (int j = 0; j < 32 * CPR / 64; ++j) {
         const int row = j * (64 / CPR) + lane / CPR;
         if (row >= r_new) {
-          *(lds_u32x4 *)(smem + (i % NB) * SLOT + Z::template offset<false>(row, c)) = knew;
-          *(lds_u32x4 *)(smem + (i % NB) * SLOT + MBYTES + Z::template offset<true>(row, c)) = vnew;
+          *(lds_u32x4 *)(const_cast<lds_char *>(sbk) + Z::template offset<false>(row, c)) = knew;
+          *(lds_u32x4 *)(const_cast<lds_char *>(sbv) + Z::template offset<true>(row, c)) = vnew;
         }
       }
       if (lane < CPR && head0 % a.group == 0) {  // one writer per (sequence, KV head)
@@ -300,8 +329,8 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     for (int r = 0; r < 16; ++r) sacc[r] = sacc1[r] = 0.f;
 #pragma unroll
     for (int s = 0; s < G::kDSteps; s += 2) {
-      bf16x8 kop0 = *(const lds_bf16x8 *)(sb + kofs[s]);
-      bf16x8 kop1 = *(const lds_bf16x8 *)(sb + kofs[s + 1]);
+      bf16x8 kop0 = *(const lds_bf16x8 *)(sbk + kofs[s]);
+      bf16x8 kop1 = *(const lds_bf16x8 *)(sbk + kofs[s + 1]);
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop0, qreg[s], sacc, 0, 0, 0);
       sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop1, qreg[s + 1], sacc1, 0, 0, 0);
     }
@@ -350,11 +379,15 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     }
     l += lsum;
     bf16x8 pop[2] = {pack8(sacc, 0), pack8(sacc, 8)};
+    if (VS) {  // behind V(i) in the queue: K(i+1) if there is one
+      if (i + 1 < nb) wait_vmcnt<NI>();
+      else wait_vmcnt<0>();
+    }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int db = 0; db < G::kDBlocks; ++db) {
-        bf16x8 vop = lds_read_vt(sb + vofs[db] + 16 * ks * ROWB, ROWB);
+        bf16x8 vop = lds_read_vt(sbv + vofs[db] + 16 * ks * ROWB, ROWB);
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
       }
     if (L <= 64) {  // very short sequences: weights as hi + lo, so bf16 rounding of P stays out of the tolerance
@@ -363,9 +396,16 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int db = 0; db < G::kDBlocks; ++db) {
-          bf16x8 vop = lds_read_vt(sb + vofs[db] + 16 * ks * ROWB, ROWB);
+          bf16x8 vop = lds_read_vt(sbv + vofs[db] + 16 * ks * ROWB, ROWB);
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[ks], o[db], 0, 0, 0);
         }
+    }
+    if (VS) {
+      // Every read of V(i) and of K(i) has been consumed by a multiply above (the scheduling
+      // barrier keeps the requests below them): their bytes may be replaced.
+      __builtin_amdgcn_sched_barrier(0);
+      if (i + 1 < nb) issue_mat(i + 1, true, 2 * MBYTES);
+      if (i + 2 < nb) issue_mat(i + 2, false, (i & 1) * MBYTES);
     }
   }
 
@@ -512,7 +552,7 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
 template <int D, int NB, bool APPEND, bool MQ = false>
 static int launch_split(const DecodeArgs &a, int batch, hipStream_t stream) {
   static bool attr_set = false;  // benign if two threads race
-  constexpr int smem = NB * 2 * 32 * D * 2;
+  constexpr int smem = (NB == 1 ? 3 : 2 * NB) * 32 * D * 2;  // NB = 1: two K blocks and one V block
   auto fn = decode_split_kernel<D, NB, APPEND, MQ>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -527,10 +567,11 @@ template <int D>
 static int launch_decode_d(DecodeArgs &a, char *out, int batch, hipStream_t stream) {
   long gy = (long)batch * a.n_hgroups;
   if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_decode: batch * head groups = %ld exceeds 65535", gy);
-  const int ring = g_ring_override > 0 ? g_ring_override : 2;  // more resident waves beat a deeper ring (measured)
+  const int ring = g_ring_override > 0 ? g_ring_override : 2;  // deeper rings and the 24 KiB form time the same or worse
   int rc;
   if (a.k_new) rc = launch_split<D, 2, true>(a, batch, stream);  // fused step: the measured-best ring only
-  else rc = ring == 2 ? launch_split<D, 2, false>(a, batch, stream)
+  else rc = ring == 1 ? launch_split<D, 1, false>(a, batch, stream)
+          : ring == 2 ? launch_split<D, 2, false>(a, batch, stream)
           : ring == 3 ? launch_split<D, 3, false>(a, batch, stream)
                       : launch_split<D, 4, false>(a, batch, stream);
   if (rc != SP_OK) return rc;

@@ -135,7 +135,7 @@ def test_tuning_keys_are_validated(built_lib):
         assert L.sp_debug_set_tuning(b"decode_chunk", v) == want
     for v, want in [(1, sp.SP_OK), (2, sp.SP_OK), (3, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"prefill_split", v) == want
-    for v, want in [(2, sp.SP_OK), (4, sp.SP_OK), (1, sp.SP_ERR_UNSUPPORTED), (5, sp.SP_ERR_UNSUPPORTED)]:
+    for v, want in [(1, sp.SP_OK), (2, sp.SP_OK), (4, sp.SP_OK), (-1, sp.SP_ERR_UNSUPPORTED), (5, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"decode_ring", v) == want
     for v, want in [(1, sp.SP_OK), (16, sp.SP_OK), (17, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"prefill_kv_splits", v) == want

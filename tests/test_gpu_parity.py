@@ -240,6 +240,23 @@ def test_fused_decode_step_c3_full():
     run_fused_steps(W.c3_decode())
 
 
+@pytest.mark.parametrize("ring", [1, 2, 3, 4])
+def test_decode_lds_ring_forms(ring):
+    """Every LDS staging form of the split kernel (ring of 2..4 K/V block pairs; 1 = two K blocks
+    and a single V block) on lengths around every block, page and split boundary."""
+    import paper_2507_11830_amd as sp
+
+    lens = np.array([1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 95, 96, 97, 128, 129, 255, 256, 257, 300, 1025, 2000])
+    sp.sp_debug_set_tuning("decode_ring", ring)
+    sp.sp_debug_set_tuning("decode_chunk", 128)
+    try:
+        run_full_compare(custom_workload(f"ring-{ring}", lens, lens - 1, 8, 1, 128, "decode", seed=81), check_cache=False)
+        run_full_compare(custom_workload(f"ring64-{ring}", lens[::2], lens[::2] - 1, 4, 2, 64, "decode", seed=82), check_cache=False)
+    finally:
+        sp.sp_debug_set_tuning("decode_ring", 0)
+        sp.sp_debug_set_tuning("decode_chunk", 0)
+
+
 @pytest.mark.parametrize("length", [5000, 12000, 20000])
 def test_decode_single_long_sequence_many_splits(length):
     """One long sequence: 40, 94 resp. 157 splits per row, so the combine pass runs its forms with
