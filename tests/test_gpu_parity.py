@@ -625,7 +625,7 @@ def test_random_shapes_against_oracle(seed):
 def test_very_long_context_chunk_and_decode():
     """A 100 000-token cached prefix (1.6 k key tiles, 6 k pages): a 48-token chunk prefilled on it
     (key range cut into the maximum number of pieces) and a fused decode step after it (782 splits,
-    eight-wave combine), both against the oracle."""
+    combine in four batches), both against the oracle."""
     lens = np.array([100048])
     w = custom_workload("long-100k", lens, lens - 48, 8, 1, 128, "prefill", seed=91)
     run_full_compare(w)
