@@ -724,6 +724,8 @@ static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, cons
   long gx = (long)batch * a.n_hgroups;
   if (gx > 0x7fffffffL || a.ntiles_x > 65535)
     return fail(SP_ERR_BAD_SHAPE, "sp_attn_prefill: grid %ld x %d exceeds the launch limits", gx, a.ntiles_x);
+  // the ranked dispatch numbers the workgroups of a launch in 32 bits
+  if (gx * a.ntiles_x * a.kv_splits > 0x7fffffffL) a.ranked = 0;
   hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)a.ntiles_x, (unsigned)a.kv_splits), dim3(512), smem, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill launch: %s", hipGetErrorString(e));
