@@ -95,8 +95,9 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  *                   long cached prefixes; with NULL / 0 (or less than that) it uses fewer
  *                   pieces or none.  The result is the same up to fp32 summation order.
  *                   Batches whose chunks are all a few tokens long (max_q_len times the query
- *                   heads per KV head <= 32: the verification step of speculative decoding)
- *                   are served, when the workspace allows, by the decode kernels —
+ *                   heads per KV head <= 32, for some shapes <= 64: the verification step of
+ *                   speculative decoding) are served, when the workspace allows, by the decode
+ *                   kernels —
  *                   bandwidth-bound, all of a sequence's query tokens share one read of its
  *                   keys.
  * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax.
@@ -186,6 +187,9 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  *   "decode_ring"   32-key blocks a decode wave keeps in its LDS ring (one computed on, the
  *                   rest in flight): 0 (built-in choice), 2..4, or 1 for two K blocks and a
  *                   single V block (less LDS per wave, one more resident wave per CU).
+ *   "combine_form"  work of a wave of the log-sum-exp combine kernel: 0 (built-in choice on the row
+ *                   count), 1 (one 32-channel slice of a row), 2 (a whole row; only taken up to
+ *                   64 splits per row).
  *   "prefill_kv_splits" pieces the key range of a prefill query tile is cut into when a
  *                   workspace is given: 0 (built-in heuristic) or 1..16 (still bounded by the
  *                   workspace size).

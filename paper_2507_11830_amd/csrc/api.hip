@@ -216,6 +216,11 @@ int sp_debug_set_tuning(const char *key, int32_t value) {
     set_prefill_split(value);
     return SP_OK;
   }
+  if (!strcmp(key, "combine_form")) {
+    if (value < 0 || value > 2) return fail(SP_ERR_UNSUPPORTED, "combine_form=%d (0, 1 or 2)", value);
+    set_combine_form(value);
+    return SP_OK;
+  }
   if (!strcmp(key, "prefill_order")) {
     if (value < 0 || value > 2) return fail(SP_ERR_UNSUPPORTED, "prefill_order=%d (0, 1 or 2)", value);
     set_prefill_order(value);

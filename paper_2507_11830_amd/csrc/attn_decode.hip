@@ -45,10 +45,10 @@ static int pick_chunk(int batch, int num_q_heads, int max_seq_len, int q_len = 1
   // Longer splits amortise a wave's fixed costs (first loads, its partial, the combine pass),
   // shorter ones fill and balance the chip: aim for a few waves per CU.  Estimate with ~8 query
   // heads per split and a mean length of half the maximum; only host-side shape is used, so
-  // the workspace size is known without reading device memory.  With q_len query tokens per
-  // sequence a split's partial is q_len times larger against the same keys read, so the balance
-  // moves towards longer splits.
-  const long enough = 512 / q_len > 64 ? 512 / q_len : 64;
+  // the workspace size is known without reading device memory.  With several query tokens per
+  // sequence a split's partial is that many times larger against the same keys read, so the
+  // balance moves towards longer splits (measured on batches of 16 to 256 sequences).
+  const long enough = q_len > 1 ? 256 : 512;
   int chunk = kDecMaxChunk;
   while (chunk > kDecMinChunk) {
     long est = (long)batch * ((num_q_heads + 7) / 8) * ((long)max_seq_len / 2) / chunk;
@@ -97,9 +97,15 @@ __device__ __forceinline__ void wait_vmcnt() {
 // then hold q_cap tokens x geff heads, each column with its own causal limit, the inputs are the
 // ragged ones of sp_attn_prefill (cu_q, ctx_lens; the chunk's K/V rows are in the cache already),
 // and K/V are still read once for all of them.
-template <int D, int NB, bool APPEND, bool MQ>
-__global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
+//
+// NT = 2 (MQ only) gives the wave two column tiles, i.e. chunks of up to 2 * q_cap tokens, on the
+// same single read of K and V: every K / V operand taken from LDS feeds one multiply per tile.
+// The second set of accumulators costs nothing in residency: LDS already limits a CU to four of
+// these waves, one per SIMD, so each may use the whole register file.
+template <int D, int NB, bool APPEND, bool MQ, int NT = 1>
+__global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(DecodeArgs a) {
   static_assert(!(APPEND && MQ), "the fused append is a single-token step");
+  static_assert(NT == 1 || MQ, "several column tiles only make sense with several query tokens");
   using G = TileGeom<D>;
   using Z = SwzTile<D>;
   constexpr int ROWB = D * 2;           // bytes of one K or V row
@@ -136,37 +142,43 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   // Entries past the sequence end are fetched too (index clamped to the table) and never used.
   int my_page = bt_row[min((kv0 >> 4) + lane, a.max_pages - 1)];
   // Column -> (query token, head) of the tile, and the row of q / out / the partials it stands for.
-  int L, ctx = 0, kv_end, lim_min = 0, lim_col = 0;
-  bool col_valid;
-  long row_col;
+  int L, ctx = 0, kv_end, lim_min = 0, lim_col[NT];
+  bool col_valid[NT];
+  long row_col[NT];
   if (MQ) {
     const int tok0 = a.cu_q[seq];
     const int qn = a.cu_q[seq + 1] - tok0;
     ctx = a.ctx_lens[seq];
-    const int t = col / a.geff, h_col = col - t * a.geff;  // the host made sure that qn <= q_cap
     if (qn <= 0) return;  // no query token: no output row, no partial
-    col_valid = t < min(qn, a.q_cap) && h_col < ncols;
-    row_col = (long)(tok0 + t) * a.Hq + head0 + h_col;
     L = ctx + qn;
     kv_end = L;          // keys visible to the chunk's last token
     lim_min = ctx + 1;   // keys visible to its first token
-    lim_col = col_valid ? ctx + t + 1 : kv_end;
+    const int t0 = col / a.geff, h_col = col - t0 * a.geff;  // the host made sure that qn <= NT * q_cap
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int t = nt * a.q_cap + t0;  // tile nt holds the tokens nt * q_cap .. (nt + 1) * q_cap - 1
+      col_valid[nt] = t0 < a.q_cap && t < qn && h_col < ncols;
+      row_col[nt] = (long)(tok0 + t) * a.Hq + head0 + h_col;
+      lim_col[nt] = col_valid[nt] ? ctx + t + 1 : kv_end;
+    }
   } else {
-    col_valid = col < ncols;
-    row_col = (long)seq * a.Hq + head0 + col;
+    col_valid[0] = col < ncols;
+    row_col[0] = (long)seq * a.Hq + head0 + col;
+    lim_col[0] = 0;
     L = 0;  // loaded below, after the query rows are requested
     kv_end = 0;
   }
-  bf16x8 qreg[G::kDSteps];
-  {
-    const char *qrow = a.q + row_col * (D * 2);
+  bf16x8 qreg[NT][G::kDSteps];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const char *qrow = a.q + row_col[nt] * (D * 2);
 #pragma unroll
     for (int s = 0; s < G::kDSteps; ++s) {
-      if (col_valid) {
-        qreg[s] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * s + 16 * half);
+      if (col_valid[nt]) {
+        qreg[nt][s] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * s + 16 * half);
       } else {
         u32x4 z = {0, 0, 0, 0};
-        qreg[s] = *reinterpret_cast<bf16x8 *>(&z);
+        qreg[nt][s] = *reinterpret_cast<bf16x8 *>(&z);
       }
     }
   }
@@ -184,8 +196,10 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     kv_end = L;
   }
   if (kv0 >= kv_end) {  // nothing to attend to: an empty partial, so the combine pass needs no lengths
-    if (lane < 32 && col_valid)
-      *reinterpret_cast<f32x2 *>(a.part_ml + (row_col * a.nsplit + split) * 2) = (f32x2){-INFINITY, 0.f};
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+      if (lane < 32 && col_valid[nt])
+        *reinterpret_cast<f32x2 *>(a.part_ml + (row_col[nt] * a.nsplit + split) * 2) = (f32x2){-INFINITY, 0.f};
     return;
   }
   const int kv1 = min(kv_end, kv0 + a.chunk);
@@ -261,14 +275,19 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
     for (int db = 0; db < G::kDBlocks; ++db)
       vofs[db] = Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) + 8 * (n & 1);
   }
-  f32x16 o[G::kDBlocks];
-#pragma unroll
-  for (int db = 0; db < G::kDBlocks; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  f32x16 o[NT][G::kDBlocks];
   // MQ: a column may find every key of the wave's first blocks behind its causal limit; a
   // finite floor keeps exp2(m - m) defined for it (the partial is written as empty if l stays 0).
-  float m = MQ ? -1e30f : -INFINITY, l = 0.f;
+  float m[NT], l[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    m[nt] = MQ ? -1e30f : -INFINITY;
+    l[nt] = 0.f;
+#pragma unroll
+    for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[nt][db][r] = 0.f;
+  }
 
   if (VS) {  // requests are made in the order K0 V0 K1 | V1 K2 | V2 K3 | ... and retire in that order
     issue_mat(0, false, 0);
@@ -324,61 +343,71 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
       wave_lds_fence();
     }
 
-    f32x16 sacc, sacc1;  // two accumulators halve the dependent MFMA chain a lone wave sits through
+    f32x16 sacc[NT], sacc1[NT];  // two accumulators per tile halve the dependent MFMA chain a lone wave sits through
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] = sacc1[r] = 0.f;
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[nt][r] = sacc1[nt][r] = 0.f;
 #pragma unroll
     for (int s = 0; s < G::kDSteps; s += 2) {
       bf16x8 kop0 = *(const lds_bf16x8 *)(sbk + kofs[s]);
       bf16x8 kop1 = *(const lds_bf16x8 *)(sbk + kofs[s + 1]);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop0, qreg[s], sacc, 0, 0, 0);
-      sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop1, qreg[s + 1], sacc1, 0, 0, 0);
-    }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] += sacc1[r];
-    if (MQ) {
-      if (base + 32 > min(lim_min, kv1)) {  // the block reaches into the chunk: per-column causal limit
-        const int lim = min(lim_col, kv1);
+      for (int nt = 0; nt < NT; ++nt) {
+        sacc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop0, qreg[nt][s], sacc[nt], 0, 0, 0);
+        sacc1[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kop1, qreg[nt][s + 1], sacc1[nt], 0, 0, 0);
+      }
+    }
+    bf16x8 pop[NT][2];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[nt][r] += sacc1[nt][r];
+      if (MQ) {
+        if (base + 32 > min(lim_min, kv1)) {  // the block reaches into the chunk: per-column causal limit
+          const int lim = min(lim_col[nt], kv1);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (kv >= lim) sacc[nt][r] = -INFINITY;
+          }
+        }
+      } else if (base + 32 > kv1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (kv >= lim) sacc[r] = -INFINITY;
+          if (kv >= kv1) sacc[nt][r] = -INFINITY;
         }
       }
-    } else if (base + 32 > kv1) {
+      float mx = sacc[nt][0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[nt][r]);
+      mx = fmaxf(mx, other_half(mx));
+      // The running max only moves when some column's block max exceeds it by more than 2^8 in
+      // the exponent (tau); otherwise weights are taken against the stale max (bounded by 2^8,
+      // harmless in fp32/bf16) and the O accumulators need no rescale.
+      if (__builtin_amdgcn_ballot_w64(mx > m[nt] + a.tau) != 0) {  // wave-uniform, rare after the first block
+        const float m_new = fmaxf(m[nt], mx);
+        const float alpha = __builtin_amdgcn_exp2f((m[nt] - m_new) * a.sl2e);
+        m[nt] = m_new;
+        l[nt] *= alpha;
+#pragma unroll
+        for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[nt][db][r] *= alpha;
+      }
+      const float msc = m[nt] * a.sl2e;
+      float lsum = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        int kv = base + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (kv >= kv1) sacc[r] = -INFINITY;
+        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[nt][r], a.sl2e, -msc));
+        sacc[nt][r] = p;
+        lsum += p;
       }
+      l[nt] += lsum;
+      pop[nt][0] = pack8(sacc[nt], 0);
+      pop[nt][1] = pack8(sacc[nt], 8);
     }
-    float mx = sacc[0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-    mx = fmaxf(mx, other_half(mx));
-    // The running max only moves when some column's block max exceeds it by more than 2^8 in
-    // the exponent (tau); otherwise weights are taken against the stale max (bounded by 2^8,
-    // harmless in fp32/bf16) and the O accumulators need no rescale.
-    if (__builtin_amdgcn_ballot_w64(mx > m + a.tau) != 0) {  // wave-uniform, rare after the first block
-      const float m_new = fmaxf(m, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * a.sl2e);
-      m = m_new;
-      l *= alpha;
-#pragma unroll
-      for (int db = 0; db < G::kDBlocks; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-    }
-    const float msc = m * a.sl2e;
-    float lsum = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[r], a.sl2e, -msc));
-      sacc[r] = p;
-      lsum += p;
-    }
-    l += lsum;
-    bf16x8 pop[2] = {pack8(sacc, 0), pack8(sacc, 8)};
     if (VS) {  // behind V(i) in the queue: K(i+1) if there is one
       if (i + 1 < nb) wait_vmcnt<NI>();
       else wait_vmcnt<0>();
@@ -388,16 +417,25 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
 #pragma unroll
       for (int db = 0; db < G::kDBlocks; ++db) {
         bf16x8 vop = lds_read_vt(sbv + vofs[db] + 16 * ks * ROWB, ROWB);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[ks], o[db], 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          o[nt][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[nt][ks], o[nt][db], 0, 0, 0);
       }
     if (L <= 64) {  // very short sequences: weights as hi + lo, so bf16 rounding of P stays out of the tolerance
-      bf16x8 plo[2] = {pack8_residual(sacc, 0, pop[0]), pack8_residual(sacc, 8, pop[1])};
+      bf16x8 plo[NT][2];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        plo[nt][0] = pack8_residual(sacc[nt], 0, pop[nt][0]);
+        plo[nt][1] = pack8_residual(sacc[nt], 8, pop[nt][1]);
+      }
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int db = 0; db < G::kDBlocks; ++db) {
           bf16x8 vop = lds_read_vt(sbv + vofs[db] + 16 * ks * ROWB, ROWB);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[ks], o[db], 0, 0, 0);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            o[nt][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, plo[nt][ks], o[nt][db], 0, 0, 0);
         }
     }
     if (VS) {
@@ -410,18 +448,21 @@ __global__ __launch_bounds__(64, 2) void decode_split_kernel(DecodeArgs a) {
   }
 
   // ---- the wave's partial: un-normalised o, m in log2 units, l
-  l += other_half(l);
-  if (col_valid) {
-    const long pidx = row_col * a.nsplit + split;
-    float *po = a.part_o + pidx * D;
 #pragma unroll
-    for (int db = 0; db < G::kDBlocks; ++db)
+  for (int nt = 0; nt < NT; ++nt) {
+    const float lt = l[nt] + other_half(l[nt]);
+    if (col_valid[nt]) {
+      const long pidx = row_col[nt] * a.nsplit + split;
+      float *po = a.part_o + pidx * D;
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-        *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * r4 + 4 * half) =
-            (f32x4){o[db][4 * r4], o[db][4 * r4 + 1], o[db][4 * r4 + 2], o[db][4 * r4 + 3]};
-    if (half == 0)
-      *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){MQ && l == 0.f ? -INFINITY : m * a.sl2e, l};
+      for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *reinterpret_cast<f32x4 *>(po + 32 * db + 8 * r4 + 4 * half) =
+              (f32x4){o[nt][db][4 * r4], o[nt][db][4 * r4 + 1], o[nt][db][4 * r4 + 2], o[nt][db][4 * r4 + 3]};
+      if (half == 0)
+        *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){MQ && lt == 0.f ? -INFINITY : m[nt] * a.sl2e, lt};
+    }
   }
 }
 
@@ -458,32 +499,41 @@ __device__ __forceinline__ float wave_max(float x) {
 // accumulates the splits g, g + 8, g + 16, ... in that order and the eight groups are then added in
 // a fixed butterfly, so the result does not depend on timing.  A row with no keys at all (every
 // m = -inf) is written as zeros.
-template <int D, int NB>
+template <int D, int NB, int SPW>
 __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ part_o,
                                                      const float *__restrict__ part_ml,
                                                      char *__restrict__ out, int nsplit) {
+  // SPW = slices per wave: 1, or all D / 32 slices of the row when there are so many rows that
+  // the launch would otherwise be tens of thousands of waves that each wait one round trip for
+  // half a KiB (the weights are then computed once per row instead of once per slice).
   constexpr int SL = D / 32;  // slices per row
-  const long row = blockIdx.x / SL;
-  const int sl = (int)(blockIdx.x - row * SL);
+  static_assert(SPW == 1 || SPW == SL, "a wave takes one slice or the whole row");
+  const long row = SPW == 1 ? blockIdx.x / SL : blockIdx.x;
+  const int sl0 = SPW == 1 ? (int)(blockIdx.x - row * SL) : 0;
   const int lane = threadIdx.x;
-  const int g = lane >> 3, ch = sl * 32 + (lane & 7) * 4;
-  bf16x4 *dst = reinterpret_cast<bf16x4 *>(out + (row * D + ch) * 2);
+  const int g = lane >> 3, ch = sl0 * 32 + (lane & 7) * 4;
+  char *dst = out + (row * D + ch) * 2;  // slice p of the wave: + 64 p bytes
   if (part_o == nullptr) {  // every sequence of the batch is empty
-    if (g == 0) *dst = __builtin_convertvector((f32x4){0.f, 0.f, 0.f, 0.f}, bf16x4);
+#pragma unroll
+    for (int p = 0; p < SPW; ++p)
+      if (g == 0) *reinterpret_cast<bf16x4 *>(dst + 64 * p) = __builtin_convertvector((f32x4){0.f, 0.f, 0.f, 0.f}, bf16x4);
     return;
   }
   const f32x2 *ml = reinterpret_cast<const f32x2 *>(part_ml) + row * nsplit;
   const float *po = part_o + row * nsplit * D + ch;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  f32x4 acc[SPW];
+#pragma unroll
+  for (int p = 0; p < SPW; ++p) acc[p] = (f32x4){0.f, 0.f, 0.f, 0.f};
   float den = 0.f, M = -INFINITY;
   for (int base = 0; base < nsplit; base += 8 * NB) {
     f32x2 w[NB];
-    f32x4 v[NB];
+    f32x4 v[SPW][NB];
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int sc = min(base + 8 * u + g, nsplit - 1);  // past the end: the last split again, weight forced to 0
       w[u] = ml[sc];
-      v[u] = *reinterpret_cast<const f32x4 *>(po + (long)sc * D);
+#pragma unroll
+      for (int p = 0; p < SPW; ++p) v[p][u] = *reinterpret_cast<const f32x4 *>(po + (long)sc * D + 32 * p);
     }
     // Everything above is in flight before anything below waits for it; the code below has no
     // branches either (given one, the compiler moves the row loads behind it, i.e. behind the wait
@@ -494,7 +544,8 @@ __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ p
     for (int u = 0; u < NB; ++u) mb = fmaxf(mb, base + 8 * u + g < nsplit ? w[u][0] : -INFINITY);
     const float Mn = fmaxf(M, wave_max(mb));                               // still -inf: only empty splits so far
     const float alpha = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - Mn);  // rescale of what has been accumulated
-    acc *= alpha;
+#pragma unroll
+    for (int p = 0; p < SPW; ++p) acc[p] *= alpha;
     den *= alpha;
     M = Mn;
 #pragma unroll
@@ -503,7 +554,9 @@ __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ p
       const float f = live ? __builtin_amdgcn_exp2f(w[u][0] - M) : 0.f;
       den += live ? f * w[u][1] : 0.f;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[j] += live ? f * v[u][j] : 0.f;
+      for (int p = 0; p < SPW; ++p)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[p][j] += live ? f * v[p][u][j] : 0.f;
     }
   }
   // the eight lane groups hold disjoint sets of splits of the same channels
@@ -511,37 +564,49 @@ __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ p
   for (int o = 8; o <= 32; o <<= 1) {
     den += __shfl_xor(den, o);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] += __shfl_xor(acc[j], o);
+    for (int p = 0; p < SPW; ++p)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[p][j] += __shfl_xor(acc[p][j], o);
   }
   if (g != 0) return;
-  if (M == -INFINITY) {
-    *dst = __builtin_convertvector((f32x4){0.f, 0.f, 0.f, 0.f}, bf16x4);
-    return;
-  }
-  const float inv = 1.0f / den;
-  *dst = __builtin_convertvector(acc * inv, bf16x4);
+  const float inv = M == -INFINITY ? 0.f : 1.0f / den;  // a row without keys: zeros
+#pragma unroll
+  for (int p = 0; p < SPW; ++p)
+    *reinterpret_cast<bf16x4 *>(dst + 64 * p) =
+        __builtin_convertvector(M == -INFINITY ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[p] * inv, bf16x4);
 }
+
+static int g_combine_rows_per_wave = 0;  // tuning hook: 0 heuristic, 1 one slice per wave, 2 whole rows
+void set_combine_form(int form) { g_combine_rows_per_wave = form; }
 
 int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
                    hipStream_t stream) {
   if (rows <= 0) return SP_OK;
-  const long blocks = rows * (head_dim / 32);
+  const int nb = nsplit <= 32 ? 4 : nsplit <= 64 ? 8 : nsplit <= 128 ? 16 : 32;  // >= ceil(nsplit / 8) up to 256 splits
+  const int sl = head_dim / 32;
+  // whole rows per wave once one slice per wave would be more than 16 waves per CU (and the
+  // loads of a whole row still fit the registers)
+  const bool whole = nb <= 8 && (g_combine_rows_per_wave == 0 ? rows * sl > 4096 : g_combine_rows_per_wave == 2);
+  const long blocks = whole ? rows : rows * sl;
   if (blocks > 0x7fffffffL) return fail(SP_ERR_BAD_SHAPE, "combine: %ld rows exceed the grid limit", rows);
   const dim3 grid((unsigned)blocks);
   char *o = (char *)out;
-  const int nb = nsplit <= 32 ? 4 : nsplit <= 64 ? 8 : nsplit <= 128 ? 16 : 32;  // >= ceil(nsplit / 8) up to 256 splits
-#define SP_COMBINE(D_, NB_) \
-  hipLaunchKernelGGL((combine_kernel<D_, NB_>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit)
+#define SP_COMBINE(D_, NB_, SPW_) \
+  hipLaunchKernelGGL((combine_kernel<D_, NB_, SPW_>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit)
   if (head_dim == 128) {
-    if (nb == 4) SP_COMBINE(128, 4);
-    else if (nb == 8) SP_COMBINE(128, 8);
-    else if (nb == 16) SP_COMBINE(128, 16);
-    else SP_COMBINE(128, 32);
+    if (whole && nb == 4) SP_COMBINE(128, 4, 4);
+    else if (whole) SP_COMBINE(128, 8, 4);
+    else if (nb == 4) SP_COMBINE(128, 4, 1);
+    else if (nb == 8) SP_COMBINE(128, 8, 1);
+    else if (nb == 16) SP_COMBINE(128, 16, 1);
+    else SP_COMBINE(128, 32, 1);
   } else {
-    if (nb == 4) SP_COMBINE(64, 4);
-    else if (nb == 8) SP_COMBINE(64, 8);
-    else if (nb == 16) SP_COMBINE(64, 16);
-    else SP_COMBINE(64, 32);
+    if (whole && nb == 4) SP_COMBINE(64, 4, 2);
+    else if (whole) SP_COMBINE(64, 8, 2);
+    else if (nb == 4) SP_COMBINE(64, 4, 1);
+    else if (nb == 8) SP_COMBINE(64, 8, 1);
+    else if (nb == 16) SP_COMBINE(64, 16, 1);
+    else SP_COMBINE(64, 32, 1);
   }
 #undef SP_COMBINE
   hipError_t e = hipGetLastError();
@@ -549,11 +614,11 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
   return SP_OK;
 }
 
-template <int D, int NB, bool APPEND, bool MQ = false>
+template <int D, int NB, bool APPEND, bool MQ = false, int NT = 1>
 static int launch_split(const DecodeArgs &a, int batch, hipStream_t stream) {
   static bool attr_set = false;  // benign if two threads race
   constexpr int smem = (NB == 1 ? 3 : 2 * NB) * 32 * D * 2;  // NB = 1: two K blocks and one V block
-  auto fn = decode_split_kernel<D, NB, APPEND, MQ>;
+  auto fn = decode_split_kernel<D, NB, APPEND, MQ, NT>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return fail(SP_ERR_HIP, "decode smem attribute: %s", hipGetErrorString(e));
@@ -592,18 +657,23 @@ static void set_head_groups(DecodeArgs &a, int num_q_heads, int num_kv_heads) {
 }
 
 // ---- short query chunks (sp_attn_prefill with a few tokens per sequence) on the split kernel
-// A chunk qualifies when its tokens x the heads of a tile fit the 32 tile columns.  (Longer chunks
-// on several tiles per sequence re-read the keys once per tile and measured slower than the
-// prefill kernel.)
-static bool multi_shape(int max_q_len, int num_q_heads, int num_kv_heads, DecodeArgs *a) {
+// A chunk qualifies when its tokens x the heads of a tile fit one 32-column tile of a wave, or
+// two where that measured faster than the prefill kernel: with at most four heads per KV head
+// (the prefill kernel then fills a quarter of its columns or less) and on small batches (which
+// leave the prefill kernel's workgroups few and long).  Further tiles in further waves re-read
+// the keys once per wave and measured slower than the prefill kernel.  Returns the number of
+// tiles, 0 if the shape does not qualify.
+static int multi_shape(int batch, int max_q_len, int num_q_heads, int num_kv_heads, DecodeArgs *a) {
   set_head_groups(*a, num_q_heads, num_kv_heads);
-  return max_q_len > 0 && max_q_len <= a->q_cap;
+  if (max_q_len <= 0 || max_q_len > 2 * a->q_cap) return 0;
+  if (max_q_len <= a->q_cap) return 1;
+  return a->geff <= 4 || (long)batch * a->n_hgroups <= 32 ? 2 : 0;
 }
 
 size_t decode_multi_workspace_bytes(int batch, int total_q, int max_q_len, int max_kv_len, int num_q_heads,
                                     int num_kv_heads, int head_dim) {
   DecodeArgs a;
-  if (max_kv_len <= 0 || total_q <= 0 || !multi_shape(max_q_len, num_q_heads, num_kv_heads, &a)) return 0;
+  if (max_kv_len <= 0 || total_q <= 0 || multi_shape(batch, max_q_len, num_q_heads, num_kv_heads, &a) == 0) return 0;
   if ((long)batch * a.n_hgroups > 65535) return 0;
   const int chunk = pick_chunk(batch, num_q_heads, max_kv_len, max_q_len);
   const size_t nsplit = (size_t)(max_kv_len + chunk - 1) / chunk;
@@ -620,7 +690,7 @@ int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const 
                                                    c.num_kv_heads, c.head_dim);
   if (need == 0 || !workspace || workspace_bytes < need) return 1;
   DecodeArgs a;
-  multi_shape(max_q_len, num_q_heads, c.num_kv_heads, &a);
+  const int tiles = multi_shape(batch, max_q_len, num_q_heads, c.num_kv_heads, &a);
   a.k_pages = (const char *)c.k_pages;
   a.v_pages = (const char *)c.v_pages;
   a.k_new = a.v_new = nullptr;
@@ -637,8 +707,13 @@ int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const 
   a.nsplit = (max_kv_len + a.chunk - 1) / a.chunk;
   a.part_o = (float *)workspace;
   a.part_ml = a.part_o + (size_t)total_q * num_q_heads * a.nsplit * c.head_dim;
-  int rc = c.head_dim == 128 ? launch_split<128, 2, false, true>(a, batch, stream)
-                             : launch_split<64, 2, false, true>(a, batch, stream);
+  int rc;
+  if (tiles == 1)
+    rc = c.head_dim == 128 ? launch_split<128, 2, false, true>(a, batch, stream)
+                           : launch_split<64, 2, false, true>(a, batch, stream);
+  else
+    rc = c.head_dim == 128 ? launch_split<128, 2, false, true, 2>(a, batch, stream)
+                           : launch_split<64, 2, false, true, 2>(a, batch, stream);
   if (rc != SP_OK) return rc;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "short-chunk split launch: %s", hipGetErrorString(e));

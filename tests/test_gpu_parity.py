@@ -240,6 +240,28 @@ def test_fused_decode_step_c3_full():
     run_fused_steps(W.c3_decode())
 
 
+@pytest.mark.parametrize("form", [1, 2])
+def test_combine_kernel_forms(form):
+    """Both work divisions of the combine kernel (a wave per 32-channel slice, a wave per whole
+    row) behind a decode batch (32 and 64 splits per row), a short-chunk batch and a prefill whose
+    key ranges are cut into pieces, head_dim 128 and 64."""
+    import paper_2507_11830_amd as sp
+
+    sp.sp_debug_set_tuning("combine_form", form)
+    sp.sp_debug_set_tuning("decode_chunk", 128)
+    sp.sp_debug_set_tuning("prefill_kv_splits", 5)
+    try:
+        lens = np.array([4000, 1, 130, 2049, 0, 777])
+        dec = np.where(lens > 0, lens, 1)
+        run_full_compare(custom_workload(f"comb-d-{form}", dec, dec - 1, 8, 1, 128, "decode", seed=85), check_cache=False)
+        run_full_compare(custom_workload(f"comb-d64-{form}", 2 * dec, 2 * dec - 1, 4, 2, 64, "decode", seed=86), check_cache=False)
+        run_full_compare(custom_workload(f"comb-s-{form}", lens + 3, lens, 8, 1, 128, "prefill", seed=87), check_cache=False)
+        run_full_compare(custom_workload(f"comb-p-{form}", lens + 40, lens, 8, 1, 128, "prefill", seed=88), check_cache=False)
+    finally:
+        for key in ("combine_form", "decode_chunk", "prefill_kv_splits"):
+            sp.sp_debug_set_tuning(key, 0)
+
+
 @pytest.mark.parametrize("ring", [1, 2, 3, 4])
 def test_decode_lds_ring_forms(ring):
     """Every LDS staging form of the split kernel (ring of 2..4 K/V block pairs; 1 = two K blocks
@@ -296,6 +318,14 @@ SHORT_CHUNK_CASES = {
     "g5": (5, 1, 128, [6, 1, 5], [400, 129, 1000]),      # 6 tokens x 5 heads = 30 of 32 columns
     "d64": (8, 2, 64, [8, 5, 2], [333, 1025, 0]),
     "fresh": (8, 1, 128, [4, 3, 1], [0, 0, 0]),          # nothing cached: a prefill of a few tokens
+    # chunks of up to twice that: two column tiles per wave on one read of the keys
+    "g8-2t": (8, 1, 128, [8, 5, 7, 1, 0, 6, 8, 4], [1000, 37, 4095, 512, 16, 0, 99, 2300]),
+    "g8-2t-straddle": (8, 1, 128, [8, 8, 8, 6, 7, 5], [121, 124, 127, 250, 1020, 509]),
+    "g4-2t": (32, 8, 128, [16, 9, 12, 1], [700, 2049, 64, 130]),
+    "g1-2t": (4, 4, 128, [64, 33, 1], [200, 1500, 33]),
+    "g5-2t": (5, 1, 128, [12, 7, 5], [400, 129, 1000]),
+    "d64-2t": (8, 2, 64, [16, 9, 2], [333, 1025, 0]),
+    "fresh-2t": (8, 1, 128, [8, 3, 5], [0, 0, 0]),
 }
 
 
@@ -331,6 +361,7 @@ def test_short_chunks_with_small_splits():
     sp.sp_debug_set_tuning("decode_chunk", 128)
     try:
         run_full_compare(custom_workload("short-128", ctx + new, ctx, 8, 1, 128, "prefill", seed=62))
+        run_full_compare(custom_workload("short-128-2t", ctx + 2 * new - 1, ctx, 8, 1, 128, "prefill", seed=63))
     finally:
         sp.sp_debug_set_tuning("decode_chunk", 0)
 
@@ -613,8 +644,8 @@ def test_random_shapes_against_oracle(seed):
     ctx = np.minimum(ctx, np.maximum(total - 1, 0))
     print(f"[shape] seed {seed}: Hq {Hkv * G} Hkv {Hkv} d {d} total {total.tolist()} ctx {ctx.tolist()}", flush=True)
     run_full_compare(custom_workload(f"rand-p-{seed}", total, ctx, Hkv * G, Hkv, d, "prefill", seed=2000 + seed))
-    # the same sequences with a chunk of at most 32 / G tokens each: the short-chunk path
-    short = np.minimum(rng.integers(0, max(32 // min(G, 32), 1) + 1, size=B), total)
+    # the same sequences with a chunk of at most 2 * 32 / G tokens each: the short-chunk path
+    short = np.minimum(rng.integers(0, 2 * max(32 // min(G, 32), 1) + 1, size=B), total)
     if short.max() > 0:
         run_full_compare(custom_workload(f"rand-s-{seed}", total, total - short, Hkv * G, Hkv, d, "prefill", seed=5000 + seed))
     dec = np.where(total > 0, total, 1)
