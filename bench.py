@@ -245,6 +245,7 @@ def extra_spec_verify(sp, iters=20):
         cu, ctx = _dev_i32(st.cu_new), _dev_i32(st.ctx_lens)
         sp.sp_kv_append(cache, _dev_bf16(st.k_new), _dev_bf16(st.v_new), cu, ctx, bt)
     q = _dev_bf16(st.q)
+    kn, vn = _dev_bf16(st.k_new), _dev_bf16(st.v_new)
     out = torch.empty_like(q)
     mq, mkv = int(st.new_lens.max()), int(st.seq_lens.max())
     ms = {}
@@ -256,13 +257,21 @@ def extra_spec_verify(sp, iters=20):
             fn = lambda: sp.sp_attn_prefill(cache, q, out, cu, ctx, bt, mq, mkv, float(w.scale), workspace=ws)
             _, per = time_phases([fn], iters, 3)
             ms[name] = per[0]
+            if mode == 0:   # the whole step: append + attention in two calls, and fused in one (idempotent: same rows, same slots)
+                app = lambda: sp.sp_kv_append(cache, kn, vn, cu, ctx, bt)
+                _, per = time_phases([app, fn], iters, 3)
+                ms["append_plus_attention"] = per[0] + per[1]
+                step = lambda: sp.sp_chunk_step(cache, kn, vn, q, out, cu, ctx, bt, mq, mkv, float(w.scale), workspace=ws)
+                _, per = time_phases([step], iters, 3)
+                ms["chunk_step_fused"] = per[0]
         finally:
             sp.sp_debug_set_tuning("prefill_short_chunk", 0)
     nbytes = W.decode_bytes(st.seq_lens, w.Hq, w.Hkv, w.d)
     return {"workload": "speculative verification, 64 sequences x 4 query tokens, 8q/1kv, d=128, contexts U{512..8192}",
             "ms": ms["short_chunk_path"], "GBps": nbytes / ms["short_chunk_path"] / 1e6,
             "frac_of_hbm_peak": nbytes / ms["short_chunk_path"] / 1e6 / PEAK_HBM_GBPS, "kv_bytes": nbytes,
-            "ms_general_prefill_kernel": ms["prefill_kernel"]}
+            "ms_general_prefill_kernel": ms["prefill_kernel"],
+            "ms_step_append_plus_attention": ms["append_plus_attention"], "ms_step_fused_sp_chunk_step": ms["chunk_step_fused"]}
 
 
 def extra_chunked_prefill(sp):

@@ -125,6 +125,27 @@ int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out,
                    float scale, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * sp_chunk_step — one chunk step in one call: sp_kv_append of every sequence's new tokens
+ * followed by sp_attn_prefill over them (chunked prefill, or the verification step of
+ * speculative decoding: the last accepted token plus the draft tokens).
+ *   k_new, v_new    bf16 [total_q_tokens][num_kv_heads][head_dim]: K/V of the chunks' tokens,
+ *                   packed like q (cu_seqlens_q serves both)
+ *   everything else as in sp_attn_prefill (ctx_lens = tokens cached before the chunk),
+ *   same workspace size.
+ * Where sp_attn_prefill would take its short-chunk path, the append happens inside the attention
+ * kernel (the waves whose key range holds the new positions fetch the rows, use them and store
+ * them to their pages): one launch less in a launch-bound step.  Otherwise the call is
+ * sp_kv_append + sp_attn_prefill.  Either way the cache afterwards holds the new rows exactly
+ * as sp_kv_append would have written them and `out` equals sp_attn_prefill's on that cache.
+ */
+int sp_chunk_step(const sp_cache_desc *cache, const void *k_new, const void *v_new,
+                  const void *q, void *out, const int32_t *cu_seqlens_q,
+                  const int32_t *ctx_lens, const int32_t *block_table, int32_t batch,
+                  int32_t max_pages_per_seq, int32_t total_q_tokens, int32_t max_q_len,
+                  int32_t max_kv_len, int32_t num_q_heads, float scale, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
  * sp_decode_step — one decode step in one call: sp_kv_append of one new token per sequence
  * followed by sp_attn_decode, with the append done inside the attention kernel (the step in
  * front of the TP-mode attention fused into it; a decode step is launch-bound, and this removes

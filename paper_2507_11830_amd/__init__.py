@@ -23,7 +23,7 @@ SP_ERR_WORKSPACE = -4
 SP_ERR_HIP = -5
 
 EXPORTS = (
-    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_decode_step", "sp_ulysses_pack", "sp_ulysses_unpack",
+    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_decode_step", "sp_chunk_step", "sp_ulysses_pack", "sp_ulysses_unpack",
     "sp_attn_prefill_workspace_size",
     "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_set_tuning",
     "sp_debug_ceiling_mfma", "sp_debug_ceiling_stream", "sp_status_string",
@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
         L.sp_attn_decode.restype = ctypes.c_int
         L.sp_decode_step.argtypes = [cd, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, sz, vp]
         L.sp_decode_step.restype = ctypes.c_int
+        L.sp_chunk_step.argtypes = [cd, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                    ctypes.c_float, vp, sz, vp]
+        L.sp_chunk_step.restype = ctypes.c_int
         L.sp_ulysses_pack.argtypes = [vp, vp, i32, i32, i32, i32, vp]
         L.sp_ulysses_pack.restype = ctypes.c_int
         L.sp_ulysses_unpack.argtypes = [vp, vp, i32, i32, i32, i32, vp]
@@ -205,6 +208,19 @@ def sp_decode_step(cache: KVCache, k_new, v_new, q, out, seq_lens, block_table, 
     _check(lib().sp_decode_step(ctypes.byref(cache.desc), _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(out),
                                 _ptr(seq_lens), _ptr(block_table), batch, max_pages, max_seq_len, num_q_heads,
                                 float(scale), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def sp_chunk_step(cache: KVCache, k_new, v_new, q, out, cu_seqlens_q, ctx_lens, block_table, max_q_len: int,
+                  max_kv_len: int, scale: float, workspace=None, stream=None) -> None:
+    """Fused append + chunk attention: k_new, v_new bf16 [T, Hkv, d] packed like q; the rest as
+    sp_attn_prefill."""
+    batch, max_pages = block_table.shape
+    total, num_q_heads = q.shape[0], q.shape[1]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sp_chunk_step(ctypes.byref(cache.desc), _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(out),
+                               _ptr(cu_seqlens_q), _ptr(ctx_lens), _ptr(block_table), batch, max_pages, total,
+                               max_q_len, max_kv_len, num_q_heads, float(scale), _ptr(workspace), ws_bytes,
+                               _stream(stream)))
 
 
 def sp_debug_validate_metadata(cache: KVCache, seq_lens, block_table) -> None:

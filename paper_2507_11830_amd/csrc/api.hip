@@ -88,6 +88,25 @@ int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
                         workspace_bytes ? workspace : nullptr, workspace_bytes, (hipStream_t)stream);
 }
 
+int sp_chunk_step(const sp_cache_desc *cache, const void *k_new, const void *v_new, const void *q, void *out,
+                  const int32_t *cu_seqlens_q, const int32_t *ctx_lens, const int32_t *block_table,
+                  int32_t batch, int32_t max_pages_per_seq, int32_t total_q_tokens, int32_t max_q_len,
+                  int32_t max_kv_len, int32_t num_q_heads, float scale, void *workspace, size_t workspace_bytes,
+                  void *stream) {
+  if (int rc = check_cache(cache)) return rc;
+  if (int rc = check_heads(cache, num_q_heads)) return rc;
+  if (int rc = check_scale(scale)) return rc;
+  if (batch < 0 || total_q_tokens < 0 || max_pages_per_seq < 0 || max_q_len < 0 || max_kv_len < 0)
+    return fail(SP_ERR_BAD_SHAPE, "negative count in sp_chunk_step");
+  if (batch == 0 || total_q_tokens == 0 || max_q_len == 0) return SP_OK;
+  if (!k_new || !v_new || !q || !out || !cu_seqlens_q || !ctx_lens || !block_table)
+    return fail(SP_ERR_NULL, "sp_chunk_step: NULL argument");
+  if (max_pages_per_seq == 0) return fail(SP_ERR_BAD_SHAPE, "max_pages_per_seq=0 with tokens to append");
+  return launch_chunk_step(*cache, k_new, v_new, q, out, cu_seqlens_q, ctx_lens, block_table, batch,
+                           max_pages_per_seq, total_q_tokens, max_q_len, max_kv_len, num_q_heads, scale,
+                           workspace_bytes ? workspace : nullptr, workspace_bytes, (hipStream_t)stream);
+}
+
 static int decode_common(const char *name, const sp_cache_desc *cache, const void *k_new, const void *v_new,
                          const void *q, void *out, const int32_t *seq_lens, const int32_t *block_table,
                          int32_t batch, int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads,

@@ -26,7 +26,7 @@ constexpr int kDecMaxChunk = 1024;  // <= 64 pages per wave: one lane holds each
 
 struct DecodeArgs {
   const char *k_pages, *v_pages, *q;
-  const char *k_new, *v_new;  // APPEND kernels: this step's K/V rows, bf16 [batch][Hkv][D]
+  const char *k_new, *v_new;  // APPEND kernels: this step's K/V rows, bf16 [tokens][Hkv][D] (one token per sequence unless MQ)
   const int32_t *seq_lens, *block_table;
   const int32_t *cu_q, *ctx_lens;  // MQ kernels: query-token prefix sums [batch + 1], cached lengths [batch]
   float *part_o;   // [row][nsplit][D], row = token * Hq + head (one token per sequence unless MQ)
@@ -104,7 +104,6 @@ __device__ __forceinline__ void wait_vmcnt() {
 // these waves, one per SIMD, so each may use the whole register file.
 template <int D, int NB, bool APPEND, bool MQ, int NT = 1>
 __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(DecodeArgs a) {
-  static_assert(!(APPEND && MQ), "the fused append is a single-token step");
   static_assert(NT == 1 || MQ, "several column tiles only make sense with several query tokens");
   using G = TileGeom<D>;
   using Z = SwzTile<D>;
@@ -186,7 +185,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
   // requested by every wave, used by the one that owns the position
   constexpr int CPR = D / 8;  // 16-byte chunks per row
   u32x4 knew = {0, 0, 0, 0}, vnew = {0, 0, 0, 0};
-  if (APPEND) {
+  if (APPEND && !MQ) {
     const size_t noff = (((size_t)seq * a.Hkv + kvh) * CPR + (lane % CPR)) * 16;
     knew = *reinterpret_cast<const u32x4 *>(a.k_new + noff);
     vnew = *reinterpret_cast<const u32x4 *>(a.v_new + noff);
@@ -320,7 +319,40 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
       sbv = sbk + MBYTES;
     }
     const int base = kv0 + 32 * i;
-    if (APPEND && kv1 == L && i == nb - 1) {
+    if (APPEND && MQ && base + 32 > ctx) {
+      // Fused append of a short chunk: the rows of this block at positions >= ctx are not in the
+      // cache yet (the loads brought stale bytes).  Every lane fetches its 16-byte pieces of the
+      // new rows, patches the block in LDS and, for positions inside the wave's range, stores
+      // them to their pages — one writer per (position, KV head).  Rows past the end of the
+      // range take the chunk's last row: finite, and masked.  At most two blocks of a sequence
+      // reach into its chunk, so the extra round trip is paid once or twice per sequence.
+      const int tok0 = a.cu_q[seq];
+      const int c = lane % CPR;
+      const bool writer = head0 % a.group == 0;
+#pragma unroll
+      for (int j = 0; j < 32 * CPR / 64; ++j) {
+        const int row = j * (64 / CPR) + lane / CPR;
+        const int pos = base + row;
+        // page of this position, from the lane that holds it: taken by all lanes, outside the
+        // branch (a cross-lane read must not depend on which lanes the branch leaves active)
+        const int pg = __shfl(my_page, min((pos - kv0) >> 4, 63));
+        if (pos >= ctx) {
+          const int t = min(pos, L - 1) - ctx;
+          const size_t noff = (((size_t)(tok0 + t) * a.Hkv + kvh) * CPR + c) * 16;
+          const u32x4 kn = *reinterpret_cast<const u32x4 *>(a.k_new + noff);
+          const u32x4 vn = *reinterpret_cast<const u32x4 *>(a.v_new + noff);
+          *(lds_u32x4 *)(const_cast<lds_char *>(sbk) + Z::template offset<false>(row, c)) = kn;
+          *(lds_u32x4 *)(const_cast<lds_char *>(sbv) + Z::template offset<true>(row, c)) = vn;
+          if (writer && pos < kv1) {
+            const size_t dst = (size_t)(unsigned)pg * page_stride + (size_t)(pos & 15) * ROWB + c * 16;
+            *reinterpret_cast<u32x4 *>(const_cast<char *>(kpool) + dst) = kn;
+            *reinterpret_cast<u32x4 *>(const_cast<char *>(vpool) + dst) = vn;
+          }
+        }
+      }
+      wave_lds_fence();
+    }
+    if (APPEND && !MQ && kv1 == L && i == nb - 1) {
       // The block that holds position L-1 has landed (it is the last one: nothing behind it).
       // Its row for that position and the rows after it (redirected to it) are stale cache
       // bytes: overwrite them in LDS with the new row, and store the row to its page.
@@ -682,7 +714,8 @@ size_t decode_multi_workspace_bytes(int batch, int total_q, int max_q_len, int m
 
 // Returns SP_OK after launching, or 1 when the shape or the workspace does not qualify (the caller
 // then runs the general prefill kernel).
-int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
+int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
+                        const int32_t *cu_q,
                         const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                         int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
                         void *workspace, size_t workspace_bytes, hipStream_t stream) {
@@ -693,7 +726,8 @@ int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const 
   const int tiles = multi_shape(batch, max_q_len, num_q_heads, c.num_kv_heads, &a);
   a.k_pages = (const char *)c.k_pages;
   a.v_pages = (const char *)c.v_pages;
-  a.k_new = a.v_new = nullptr;
+  a.k_new = (const char *)k_new;  // both NULL: the chunk's rows are in the cache already
+  a.v_new = (const char *)v_new;
   a.q = (const char *)q;
   a.seq_lens = nullptr;
   a.cu_q = cu_q;
@@ -708,12 +742,20 @@ int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const 
   a.part_o = (float *)workspace;
   a.part_ml = a.part_o + (size_t)total_q * num_q_heads * a.nsplit * c.head_dim;
   int rc;
-  if (tiles == 1)
+  if (k_new) {  // fused append of the chunk's rows
+    if (tiles == 1)
+      rc = c.head_dim == 128 ? launch_split<128, 2, true, true>(a, batch, stream)
+                             : launch_split<64, 2, true, true>(a, batch, stream);
+    else
+      rc = c.head_dim == 128 ? launch_split<128, 2, true, true, 2>(a, batch, stream)
+                             : launch_split<64, 2, true, true, 2>(a, batch, stream);
+  } else if (tiles == 1) {
     rc = c.head_dim == 128 ? launch_split<128, 2, false, true>(a, batch, stream)
                            : launch_split<64, 2, false, true>(a, batch, stream);
-  else
+  } else {
     rc = c.head_dim == 128 ? launch_split<128, 2, false, true, 2>(a, batch, stream)
                            : launch_split<64, 2, false, true, 2>(a, batch, stream);
+  }
   if (rc != SP_OK) return rc;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "short-chunk split launch: %s", hipGetErrorString(e));

@@ -745,6 +745,22 @@ static int launch_prefill_d(const PrefillArgs &a, bool split, int batch, int max
   return launch_cfg(prefill_kernel<D, KVT, PFD, false, false>, &set[3], smem, 256, a, batch, max_q_len, stream);
 }
 
+int launch_chunk_step(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
+                      const int32_t *cu_q, const int32_t *ctx_lens, const int32_t *block_table, int batch,
+                      int max_pages, int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
+                      void *workspace, size_t workspace_bytes, hipStream_t stream) {
+  if (g_short_chunk_mode != 1) {
+    // short chunks: the decode kernels append the rows themselves
+    int rc = launch_decode_multi(c, k_new, v_new, q, out, cu_q, ctx_lens, block_table, batch, max_pages, total_q,
+                                 max_q_len, max_kv_len, num_q_heads, scale, workspace, workspace_bytes, stream);
+    if (rc != 1) return rc;
+  }
+  int rc = launch_kv_append(c, k_new, v_new, cu_q, ctx_lens, block_table, batch, max_pages, total_q, stream);
+  if (rc != SP_OK) return rc;
+  return launch_prefill(c, q, out, cu_q, ctx_lens, block_table, batch, max_pages, total_q, max_q_len, max_kv_len,
+                        num_q_heads, scale, workspace, workspace_bytes, stream);
+}
+
 int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                    int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
@@ -752,7 +768,7 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   if (g_short_chunk_mode != 1) {
     // Every chunk is a few tokens long: the bandwidth-bound split kernel of the decode path reads
     // each sequence's keys once for all of its query tokens.
-    int rc = launch_decode_multi(c, q, out, cu_q, ctx_lens, block_table, batch, max_pages, total_q, max_q_len,
+    int rc = launch_decode_multi(c, nullptr, nullptr, q, out, cu_q, ctx_lens, block_table, batch, max_pages, total_q, max_q_len,
                                  max_kv_len, num_q_heads, scale, workspace, workspace_bytes, stream);
     if (rc != 1) return rc;
   }

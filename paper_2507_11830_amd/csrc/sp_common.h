@@ -33,6 +33,12 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
                    const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                    int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
                    void *workspace, size_t workspace_bytes, hipStream_t stream);
+// Append the chunks' K/V rows, then attend (sp_chunk_step): one fused launch where the short-chunk
+// path applies, else launch_kv_append + launch_prefill.
+int launch_chunk_step(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
+                      const int32_t *cu_q, const int32_t *ctx_lens, const int32_t *block_table, int batch,
+                      int max_pages, int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
+                      void *workspace, size_t workspace_bytes, hipStream_t stream);
 size_t prefill_workspace_bytes(int batch, int total_q_tokens, int max_q_len, int max_kv_len, int num_q_heads,
                                int num_kv_heads, int head_dim);
 
@@ -64,9 +70,12 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
 // Short query chunks (a few tokens per sequence on long prefixes) on the decode split kernel:
 // same arguments as launch_prefill.  Returns 1 without launching anything when the shape or the
 // workspace does not qualify; decode_multi_workspace_bytes is 0 for shapes that never qualify.
+// k_new / v_new non-NULL: the chunks' K/V rows ([total_q][Hkv][d]) are not in the cache yet and are
+// appended by the kernel (fused chunk step).
 size_t decode_multi_workspace_bytes(int batch, int total_q, int max_q_len, int max_kv_len, int num_q_heads,
                                     int num_kv_heads, int head_dim);
-int launch_decode_multi(const sp_cache_desc &c, const void *q, void *out, const int32_t *cu_q,
+int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
+                        const int32_t *cu_q,
                         const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                         int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
                         void *workspace, size_t workspace_bytes, hipStream_t stream);

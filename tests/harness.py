@@ -66,6 +66,22 @@ class GpuRunner:
         torch.cuda.synchronize()
         return bits_of(out)
 
+    def chunk_step(self, st: W.Step):
+        """Fused append + attention of a chunk step (any chunk lengths)."""
+        import torch
+
+        w, sp = self.w, self.sp
+        assert st.kind == "prefill"
+        q = to_dev(st.q)
+        out = torch.full_like(q, float("nan"))
+        mq, mkv = int(st.new_lens.max()), int(st.seq_lens.max())
+        need = sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], mq, mkv, w.Hq, w.Hkv, w.d) if self.prefill_workspace else 0
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+        sp.sp_chunk_step(self.cache, to_dev(st.k_new), to_dev(st.v_new), q, out, dev_i32(st.cu_new),
+                         dev_i32(st.ctx_lens), self.bt, mq, mkv, float(w.scale), workspace=ws)
+        torch.cuda.synchronize()
+        return bits_of(out)
+
     def decode_step(self, st: W.Step):
         """Fused append + decode of a step in which every sequence has exactly one new token."""
         import torch

@@ -119,6 +119,9 @@ def test_argument_validation_needs_no_gpu(built_lib):
     assert L.sp_ulysses_unpack(None, one, 4, 8, 128, 2, None) == sp.SP_ERR_NULL
     assert L.sp_ulysses_unpack(None, None, 0, 8, 128, 2, None) == sp.SP_OK
     assert L.sp_decode_step(ctypes.byref(d), None, one, one, one, one, one, 4, 64, 1000, 8, 0.1, one, 1 << 30, None) == sp.SP_ERR_NULL
+    assert L.sp_chunk_step(ctypes.byref(d), None, one, one, one, one, one, one, 4, 64, 16, 4, 1000, 8, 0.1, one, 1 << 30, None) == sp.SP_ERR_NULL
+    assert L.sp_chunk_step(ctypes.byref(d), one, one, one, one, one, one, one, 4, 64, 16, 4, 1000, 0, 0.1, one, 1 << 30, None) == sp.SP_ERR_BAD_SHAPE
+    assert L.sp_chunk_step(ctypes.byref(d), one, one, one, one, one, one, one, 0, 64, 0, 0, 0, 8, 0.1, None, 0, None) == sp.SP_OK
     # empty batches are legal no-ops
     assert L.sp_attn_prefill(ctypes.byref(d), one, one, one, one, one, 0, 1, 0, 0, 0, 8, 0.1, 1, None, 0, None) == sp.SP_OK
     assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 0, 1, 0, 8, 0.1, None, 0, None) == sp.SP_OK

@@ -347,6 +347,48 @@ def test_short_chunks_on_both_kernel_paths(case, short_path):
         sp.sp_debug_set_tuning("prefill_short_chunk", 0)
 
 
+def run_chunk_steps(w):
+    """Every non-fill step through sp_chunk_step (append fused where the library can); outputs and
+    the final cache image against the oracle."""
+    g, o = GpuRunner(w), OracleRunner(w)
+    worst = 0.0
+    for i, st in enumerate(w.steps()):
+        o.append(st)
+        if st.kind == "fill":
+            g.append(st)
+        else:
+            worst = max(worst, report_err(f"{w.name} chunk step {i}", g.chunk_step(st), o.attend(st)))
+    gk, gv = g.cache_bits()
+    assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp), "cache image differs from the oracle's"
+    assert worst <= TOL
+
+
+@pytest.mark.parametrize("case", sorted(SHORT_CHUNK_CASES))
+def test_fused_chunk_step_short_chunks(case):
+    """sp_chunk_step on the short-chunk shapes: the attention kernel itself appends the chunk's
+    rows (chunks straddling block, page and split boundaries, one and two column tiles, empty
+    chunks, empty prefixes); output and cache image incl. canaries against the oracle."""
+    Hq, Hkv, d, new, ctx = SHORT_CHUNK_CASES[case]
+    new, ctx = np.array(new), np.array(ctx)
+    run_chunk_steps(custom_workload(f"chunkstep-{case}", ctx + new, ctx, Hq, Hkv, d, "prefill", seed=64))
+
+
+def test_fused_chunk_step_small_splits_and_general_chunks():
+    import paper_2507_11830_amd as sp
+
+    new = np.array([4, 4, 4, 4, 4, 4, 4, 4])
+    ctx = np.array([124, 125, 126, 127, 128, 129, 380, 1])
+    sp.sp_debug_set_tuning("decode_chunk", 128)
+    try:
+        run_chunk_steps(custom_workload("chunkstep-128", ctx + new, ctx, 8, 1, 128, "prefill", seed=65))
+        run_chunk_steps(custom_workload("chunkstep-128-2t", ctx + 2 * new - 1, ctx, 8, 1, 128, "prefill", seed=66))
+    finally:
+        sp.sp_debug_set_tuning("decode_chunk", 0)
+    # chunks too long for the short-chunk path: the call is sp_kv_append + sp_attn_prefill
+    run_chunk_steps(custom_workload("chunkstep-long", [300, 45, 1000], [100, 0, 990], 8, 1, 128, "prefill", seed=67))
+    run_chunk_steps(W.spec_verify())
+
+
 def test_spec_verify_bench_shape_full_size():
     """The 64-sequence, 4-token verification batch bench.py times, every output element."""
     run_full_compare(W.spec_verify(), check_cache=False)
