@@ -623,6 +623,51 @@ def test_decode_step_in_a_hip_graph():
     assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp)
 
 
+def test_chunk_step_in_a_hip_graph():
+    """The same for sp_chunk_step on a verification batch (append fused into the attention launch):
+    captured once, replayed with stale workspace and output contents, every replay equal to the
+    eager result, cache image equal to the oracle's."""
+    import torch
+    import paper_2507_11830_amd as sp
+
+    new = np.array([4, 2, 3, 4, 1])
+    ctx = np.array([700, 33, 0, 2049, 510])
+    w = custom_workload("graph-chunk", ctx + new, ctx, 8, 1, 128, "prefill", seed=96)
+    g, o = GpuRunner(w), OracleRunner(w)
+    fill, st = list(w.steps())
+    g.append(fill)
+    o.append(fill)
+    o.append(st)
+    want = o.attend(st)
+    k_new, v_new, q = to_dev(st.k_new), to_dev(st.v_new), to_dev(st.q)
+    cu, cx = dev_i32(st.cu_new), dev_i32(st.ctx_lens)
+    mq, mkv = int(st.new_lens.max()), int(st.seq_lens.max())
+    ws = torch.empty(sp.sp_attn_prefill_workspace_size(w.batch, q.shape[0], mq, mkv, w.Hq, w.Hkv, w.d),
+                     dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(q)
+    call = lambda: sp.sp_chunk_step(g.cache, k_new, v_new, q, out, cu, cx, g.bt, mq, mkv, float(w.scale), workspace=ws)
+    call()   # eager first: also the one-time kernel attribute set-up, outside the capture
+    torch.cuda.synchronize()
+    eager = bits_of(out).copy()
+    assert np.abs(W.bf16_bits_to_f64(eager) - want).max() <= TOL
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out.zero_()
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_of(out), eager), f"replay {rep} differs from the eager result"
+    gk, gv = g.cache_bits()
+    assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp)
+
+
 def test_c5c_full_size_sampled_sequences():
     """C5c at full size in the configuration bench.py times (128 sequences U{1024..16384}, 32q/8kv,
     about 4.7 GB of K/V drawn by torch's seeded GPU generator, the library's own launch shape):
