@@ -95,8 +95,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // tokens per sequence on a long cached prefix, causal inside the chunk; the paper combines Shift
 // Parallelism with speculative decoding in its "Arctic Inference" section).  The 32 tile columns
 // then hold q_cap tokens x geff heads, each column with its own causal limit, the inputs are the
-// ragged ones of sp_attn_prefill (cu_q, ctx_lens; the chunk's K/V rows are in the cache already),
-// and K/V are still read once for all of them.
+// ragged ones of sp_attn_prefill (cu_q, ctx_lens), and K/V are still read once for all of them.
+// With APPEND as well (sp_chunk_step) the chunk's K/V rows are not in the cache yet: the waves
+// whose key range reaches into the chunk fetch them from k_new / v_new, patch them into their
+// LDS blocks and store them to their pages.
 //
 // NT = 2 (MQ only) gives the wave two column tiles, i.e. chunks of up to 2 * q_cap tokens, on the
 // same single read of K and V: every K / V operand taken from LDS feeds one multiply per tile.
