@@ -536,7 +536,8 @@ __device__ __forceinline__ float wave_max(float x) {
 template <int D, int NB, int SPW>
 __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ part_o,
                                                      const float *__restrict__ part_ml,
-                                                     char *__restrict__ out, int nsplit) {
+                                                     char *__restrict__ out, int nsplit,
+                                                     const int32_t *__restrict__ cu_q, int batch, int Hq) {
   // SPW = slices per wave: 1, or all D / 32 slices of the row when there are so many rows that
   // the launch would otherwise be tens of thousands of waves that each wait one round trip for
   // half a KiB (the weights are then computed once per row instead of once per slice).
@@ -547,6 +548,14 @@ __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ p
   const int lane = threadIdx.x;
   const int g = lane >> 3, ch = sl0 * 32 + (lane & 7) * 4;
   char *dst = out + (row * D + ch) * 2;  // slice p of the wave: + 64 p bytes
+  // Rows of a varlen batch: only those of this call's sequences are written (a call on a
+  // sub-range of a batch's sequences must leave the other rows of `out` alone).  Requested with
+  // everything else, looked at only before the store.
+  long row_lo = 0, row_hi = 0x7fffffffffffffffL;
+  if (cu_q != nullptr) {
+    row_lo = (long)cu_q[0] * Hq;
+    row_hi = (long)cu_q[batch] * Hq;
+  }
   if (part_o == nullptr) {  // every sequence of the batch is empty
 #pragma unroll
     for (int p = 0; p < SPW; ++p)
@@ -602,7 +611,7 @@ __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ p
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[p][j] += __shfl_xor(acc[p][j], o);
   }
-  if (g != 0) return;
+  if (g != 0 || row < row_lo || row >= row_hi) return;
   const float inv = M == -INFINITY ? 0.f : 1.0f / den;  // a row without keys: zeros
 #pragma unroll
   for (int p = 0; p < SPW; ++p)
@@ -614,7 +623,7 @@ static int g_combine_rows_per_wave = 0;  // tuning hook: 0 heuristic, 1 one slic
 void set_combine_form(int form) { g_combine_rows_per_wave = form; }
 
 int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
-                   hipStream_t stream) {
+                   hipStream_t stream, const int32_t *cu_q, int batch, int num_q_heads) {
   if (rows <= 0) return SP_OK;
   const int nb = nsplit <= 32 ? 4 : nsplit <= 64 ? 8 : nsplit <= 128 ? 16 : 32;  // >= ceil(nsplit / 8) up to 256 splits
   const int sl = head_dim / 32;
@@ -626,7 +635,8 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
   const dim3 grid((unsigned)blocks);
   char *o = (char *)out;
 #define SP_COMBINE(D_, NB_, SPW_) \
-  hipLaunchKernelGGL((combine_kernel<D_, NB_, SPW_>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit)
+  hipLaunchKernelGGL((combine_kernel<D_, NB_, SPW_>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit, cu_q, batch, \
+                     num_q_heads)
   if (head_dim == 128) {
     if (whole && nb == 4) SP_COMBINE(128, 4, 4);
     else if (whole) SP_COMBINE(128, 8, 4);
@@ -761,7 +771,8 @@ int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v
   if (rc != SP_OK) return rc;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "short-chunk split launch: %s", hipGetErrorString(e));
-  return launch_combine(a.part_o, a.part_ml, out, (long)total_q * num_q_heads, a.nsplit, c.head_dim, stream);
+  return launch_combine(a.part_o, a.part_ml, out, (long)total_q * num_q_heads, a.nsplit, c.head_dim, stream, cu_q, batch,
+                        num_q_heads);
 }
 
 int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,

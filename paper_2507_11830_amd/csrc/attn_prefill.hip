@@ -840,7 +840,7 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   int rc = c.head_dim == 128 ? launch_prefill_d<128>(a, small_grid, batch, max_q_len, stream)
                              : launch_prefill_d<64>(a, small_grid, batch, max_q_len, stream);
   if (rc != SP_OK || kvs == 1) return rc;
-  return launch_combine(a.part_o, a.part_ml, out, rows, kvs, c.head_dim, stream);
+  return launch_combine(a.part_o, a.part_ml, out, rows, kvs, c.head_dim, stream, cu_q, batch, num_q_heads);
 }
 
 }  // namespace sp

@@ -57,8 +57,9 @@ void set_prefill_order(int mode);  // 0 heuristic, 1 workgroups in (tile, sequen
 // Log-sum-exp merge of per-split partials: part_o [rows][nsplit][head_dim] fp32 un-normalised,
 // part_ml [rows][nsplit][2] fp32 (max in log2 units, sum); out [rows][head_dim] bf16.
 // part_o == nullptr writes zero rows.
+// cu_q non-NULL (varlen batches): only the rows [cu_q[0], cu_q[batch]) x num_q_heads are written.
 int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
-                   hipStream_t stream);
+                   hipStream_t stream, const int32_t *cu_q = nullptr, int batch = 0, int num_q_heads = 0);
 
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);
 // k_new / v_new non-NULL: fused decode step (the new token's rows are appended by the kernel).

@@ -623,6 +623,36 @@ def test_decode_step_in_a_hip_graph():
     assert np.array_equal(gk, o.kp) and np.array_equal(gv, o.vp)
 
 
+def test_mixed_batch_split_into_two_calls():
+    """A batch of single-token sequences followed by prefill chunks, attended in two calls on
+    sub-ranges of the same metadata arrays (offset pointers; q / out and the token offsets in
+    cu_seqlens_q stay global): the decode-like part takes the short-chunk path, the chunks the
+    prefill kernel.  Same result as the oracle's one pass over the whole batch."""
+    import torch
+    import paper_2507_11830_amd as sp
+
+    new = np.array([1, 1, 1, 1, 1, 1, 300, 64])
+    ctx = np.array([700, 33, 4000, 2049, 15, 0, 100, 1500])
+    n = 6
+    w = custom_workload("mixed-split", ctx + new, ctx, 8, 1, 128, "prefill", seed=97)
+    g, o = GpuRunner(w), OracleRunner(w)
+    for st in w.steps():
+        g.append(st)
+        o.append(st)
+    want = o.attend(st)
+    q = to_dev(st.q)
+    out = torch.full_like(q, float("nan"))
+    cu, cx = dev_i32(st.cu_new), dev_i32(st.ctx_lens)
+    total = q.shape[0]
+    for lo, hi in ((n, len(new)), (0, n)):   # in either order: a call writes its own sequences' rows only
+        mq, mkv = int(st.new_lens[lo:hi].max()), int(st.seq_lens[lo:hi].max())
+        need = sp.sp_attn_prefill_workspace_size(hi - lo, total, mq, mkv, w.Hq, w.Hkv, w.d)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+        sp.sp_attn_prefill(g.cache, q, out, cu[lo:hi + 1], cx[lo:hi], g.bt[lo:hi], mq, mkv, float(w.scale), workspace=ws)
+    torch.cuda.synchronize()
+    assert report_err("mixed batch in two calls", bits_of(out), want) <= TOL
+
+
 def test_chunk_step_in_a_hip_graph():
     """The same for sp_chunk_step on a verification batch (append fused into the attention launch):
     captured once, replayed with stale workspace and output contents, every replay equal to the
