@@ -61,6 +61,7 @@ struct PrefillArgs {
   float *part_o, *part_ml;
   int kv_splits;
   int batch;
+  int total_q;     // host count of query tokens (bounds the number of work items)
   int ranked;      // workgroups take their work items heaviest first (ranked_item below)
   int rank_shift;  // log2 of the weight unit in keys
 };
@@ -724,9 +725,18 @@ static int launch_cfg(prefill_fn fn, bool *attr_set, size_t smem, int cols, cons
   long gx = (long)batch * a.n_hgroups;
   if (gx > 0x7fffffffL || a.ntiles_x > 65535)
     return fail(SP_ERR_BAD_SHAPE, "sp_attn_prefill: grid %ld x %d exceeds the launch limits", gx, a.ntiles_x);
-  // the ranked dispatch numbers the workgroups of a launch in 32 bits
-  if (gx * a.ntiles_x * a.kv_splits > 0x7fffffffL) a.ranked = 0;
-  hipLaunchKernelGGL(fn, dim3((unsigned)gx, (unsigned)a.ntiles_x, (unsigned)a.kv_splits), dim3(512), smem, stream, a);
+  dim3 grid((unsigned)gx, (unsigned)a.ntiles_x, (unsigned)a.kv_splits);
+  if (a.ranked) {
+    // Ranked workgroups take items by linear id, so the launch only needs as many workgroups as
+    // there can be items: every sequence has at most q_len / tpt + 1 query tiles.  (The grid of
+    // the static order is batch x tiles of the LONGEST chunk; in a ragged batch most of it is
+    // empty, and an empty workgroup still holds a CU for a microsecond.)
+    const long items = (long)a.total_q / tpt + batch;
+    const long wgs = items * a.n_hgroups * a.kv_splits;
+    if (wgs > 0x7fffffffL) a.ranked = 0;  // workgroups are numbered in 32 bits
+    else grid = dim3((unsigned)wgs, 1, 1);
+  }
+  hipLaunchKernelGGL(fn, grid, dim3(512), smem, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "prefill launch: %s", hipGetErrorString(e));
   return SP_OK;
@@ -830,6 +840,7 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   // sequences with cached prefixes (without prefixes the last query tiles of all sequences are
   // the heaviest items, and they are first in the static order too).
   a.batch = batch;
+  a.total_q = total_q;
   const bool can_rank = batch <= 64 * kRankSlots;
   a.ranked = can_rank && (g_order_mode == 0 ? batch >= 2 && max_kv_len > max_q_len : g_order_mode == 2);
   a.rank_shift = 6;
