@@ -68,9 +68,6 @@ size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int h
   return (size_t)batch * num_q_heads * nsplit * (head_dim + 2) * sizeof(float);
 }
 
-// s_waitcnt that waits for the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and
-// 15:14, expcnt and lgkmcnt left at their maxima).  The "memory" clobber keeps the compiler from
-// moving LDS reads of the awaited block above it.
 // Orders a wave's own LDS writes before its later LDS reads without a workgroup barrier: the
 // hardware runs one wave's LDS operations in order, so only the compiler has to be stopped from
 // moving them across this point.
@@ -80,6 +77,9 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// s_waitcnt on the vector-memory counter only (the other counters are not named, so they are
+// left alone).  The "memory" clobber keeps the compiler from moving LDS reads of the awaited
+// block above it.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
