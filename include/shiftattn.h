@@ -176,7 +176,9 @@ int sp_decode_step(const sp_cache_desc *cache, const void *k_new, const void *v_
 /* Bytes of workspace for the given host-side shape: what sp_attn_decode requires, and what lets
  * sp_attn_prefill split key ranges or take its short-chunk path (0 when neither would be used:
  * too many query rows for it to pay).  max_q_len / max_kv_len are the hints later passed to
- * sp_attn_prefill; the size is monotone in neither, so ask again when they change. */
+ * sp_attn_prefill; the sizes are not monotone in the length hints (the split length follows the
+ * shape), so ask again when the hints change: a call checks its workspace against the size for
+ * the hints it is given. */
 size_t sp_attn_prefill_workspace_size(int32_t batch, int32_t total_q_tokens, int32_t max_q_len,
                                       int32_t max_kv_len, int32_t num_q_heads,
                                       int32_t num_kv_heads, int32_t head_dim);
@@ -212,7 +214,7 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
 /*
  * sp_debug_set_tuning — process-wide override of an internal launch parameter, for tuning
  * sweeps and tests.  Not thread-safe against concurrent attention calls.  Keys:
- *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a power of two in
+ *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a multiple of 32 in
  *                   [128, 1024].  Changes what sp_attn_decode_workspace_size returns.
  *   "decode_ring"   32-key blocks a decode wave keeps in its LDS ring (one computed on, the
  *                   rest in flight): 0 (built-in choice), 2..4, or 1 for two K blocks and a

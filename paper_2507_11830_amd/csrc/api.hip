@@ -215,8 +215,8 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
 int sp_debug_set_tuning(const char *key, int32_t value) {
   if (!key) return fail(SP_ERR_NULL, "tuning key is NULL");
   if (!strcmp(key, "decode_chunk")) {
-    if (value != 0 && (value < 128 || value > 1024 || (value & (value - 1))))
-      return fail(SP_ERR_UNSUPPORTED, "decode_chunk=%d (0, or a power of two in [128, 1024])", value);
+    if (value != 0 && (value < 128 || value > 1024 || value % 32 != 0))
+      return fail(SP_ERR_UNSUPPORTED, "decode_chunk=%d (0, or a multiple of 32 in [128, 1024])", value);
     set_decode_chunk(value);
     return SP_OK;
   }

@@ -48,10 +48,21 @@ static int pick_chunk(int batch, int num_q_heads, int max_seq_len, int q_len = 1
   // the workspace size is known without reading device memory.  With several query tokens per
   // sequence a split's partial is that many times larger against the same keys read, so the
   // balance moves towards longer splits (measured on batches of 16 to 256 sequences).
+  const long tiles = (long)batch * ((num_q_heads + 7) / 8);
+  if (q_len == 1) {
+    // Single tokens: when the whole batch fits one round of resident waves (four per CU, by LDS)
+    // with splits of at most 512 keys, make it exactly one round — a second, sparsely filled
+    // round runs at a fraction of the bandwidth (C3: 1083 waves of 256 keys on 1024 slots take
+    // 34.5 us, 870 waves of 320 keys 33.0).  With longer splits the serial chain of a wave's
+    // blocks costs more than the second round (measured), and the rule below decides.
+    const long slots = 4 * 256 * 85 / 100;  // resident waves of the chip, with a margin for the estimate
+    const long one_round = (tiles * (max_seq_len / 2) / slots + 31) / 32 * 32;
+    if (one_round <= 512) return (int)(one_round < kDecMinChunk ? kDecMinChunk : one_round);
+  }
   const long enough = q_len > 1 ? 256 : 512;
   int chunk = kDecMaxChunk;
   while (chunk > kDecMinChunk) {
-    long est = (long)batch * ((num_q_heads + 7) / 8) * ((long)max_seq_len / 2) / chunk;
+    long est = tiles * ((long)max_seq_len / 2) / chunk;
     if (est >= enough) break;
     chunk /= 2;
   }
