@@ -34,8 +34,8 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
 # what the same counters read for the 1 GiB copy of `--workload copy` (FETCH_SIZE x2.000,
 # WRITE_SIZE x1.000); figures and commands in profiles/pmc_hbm_traffic_and_mfma.md.
-TRAFFIC_PREFILL_C2 = int(17436.0 * 1024 * 2.0 + 16384.1 * 1024)
-TRAFFIC_DECODE_C3 = int((68106.3 + 4374.0) * 1024 * 2.0 + (4850.4 + 128.0) * 1024)
+TRAFFIC_PREFILL_C2 = int(17416.8 * 1024 * 2.0 + 16384.3 * 1024)
+TRAFFIC_DECODE_C3 = int((68030.6 + 3666.5) * 1024 * 2.0 + (3892.0 + 128.0) * 1024)
 
 
 def _dev_bf16(u16):
