@@ -373,6 +373,27 @@ def test_fused_chunk_step_short_chunks(case):
     run_chunk_steps(custom_workload(f"chunkstep-{case}", ctx + new, ctx, Hq, Hkv, d, "prefill", seed=64))
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_fused_chunk_step_random_batches(seed):
+    """Seeded random batches (head configuration, head_dim, prefixes, chunks of 0 .. 2 x 32/G
+    tokens, now and then a chunk too long for the fused path) through sp_chunk_step: outputs and
+    cache image against the oracle."""
+    rng = np.random.default_rng(7000 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 12))
+    ctx = rng.integers(0, int(rng.choice([40, 300, 1500, 5000])) + 1, size=B)
+    two_tiles = 2 * max(32 // min(G, 32), 1)
+    new = rng.integers(0, two_tiles + 1, size=B)
+    if rng.random() < 0.25:
+        new[rng.integers(0, B)] = int(rng.integers(two_tiles + 1, 200))
+    if new.max() == 0:
+        new[0] = 1
+    print(f"[shape] seed {seed}: Hq {Hkv * G} Hkv {Hkv} d {d} new {new.tolist()} ctx {ctx.tolist()}", flush=True)
+    run_chunk_steps(custom_workload(f"rand-chunk-{seed}", ctx + new, ctx, Hkv * G, Hkv, d, "prefill", seed=8000 + seed))
+
+
 def test_fused_chunk_step_small_splits_and_general_chunks():
     import paper_2507_11830_amd as sp
 
