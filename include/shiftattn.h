@@ -84,8 +84,8 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  *   ctx_lens        int32 [batch] tokens cached BEFORE this chunk; the chunk's own K/V must
  *                   already have been appended (query i of sequence s is at ctx_lens[s] + i)
  *   max_q_len       host hint: >= the longest chunk in the batch (sizes the grid)
- *   max_kv_len      host hint: >= the largest ctx_lens[s] + chunk length (unused rows cost
- *                   nothing; it only bounds loops)
+ *   max_kv_len      host hint: >= the largest ctx_lens[s] + chunk length (sizes launches and
+ *                   the workspace; keys beyond it may be ignored)
  *   scale           softmax scale, normally 1/sqrt(head_dim)
  *   causal          must be 1
  *   workspace       optional device scratch (contents need no initialisation).  With at least
@@ -97,9 +97,8 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  *                   Batches whose chunks are all a few tokens long (max_q_len times the query
  *                   heads per KV head <= 32, for some shapes <= 64: the verification step of
  *                   speculative decoding) are served, when the workspace allows, by the decode
- *                   kernels —
- *                   bandwidth-bound, all of a sequence's query tokens share one read of its
- *                   keys.
+ *                   kernels: bandwidth-bound, all of a sequence's query tokens share one read
+ *                   of its keys.
  * Sub-ranges.  The call touches only the rows of `out` that belong to its sequences, so a batch
  * may be attended in several calls on sub-ranges of its sequences: keep q, out and
  * total_q_tokens, advance cu_seqlens_q, ctx_lens and block_table to the first sequence of the
