@@ -352,6 +352,38 @@ def test_sampled_rows_match_full_prefill(oracle):
         assert np.array_equal(got[i], full[cuq[rs[i]] + rt[i], rh[i]])
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(6, 2), (8, 4), (12, 3)])
+def test_sampled_rows_gqa_head_map(oracle, Hq, Hkv):
+    """The sampled-row driver with several KV heads and several query heads per KV head (Hkv >= 2,
+    G >= 2): query head h must read KV head h // G, as in the full driver (pinned by P1/P2/P10) and
+    as in an independent dense computation of the same rows.  A contiguous-versus-strided head map
+    (h % Hkv) gives a different KV head for some sampled head at every shape here."""
+    rng = rng_for(f"rows-gqa-{Hq}-{Hkv}")
+    G, d = Hq // Hkv, 8
+    lens = [23, 41, 17]
+    kp, vp, bt, ks, vs, cu = paged_setup(oracle, rng, lens, Hkv, d)
+    ctx = np.array([5, 0, 16], np.int32)
+    n = np.array(lens, np.int32) - ctx
+    cuq = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+    q = bits(rng, (int(n.sum()), Hq, d))
+    full = oracle.attn_prefill(kp, vp, q, cuq, ctx, bt, 0.4)
+    rs, rt, rh = [], [], []
+    for s in range(3):                      # every head on a first, a middle and a last row
+        for t in (0, int(n[s]) // 2, int(n[s]) - 1):
+            for h in range(Hq):
+                rs.append(s), rt.append(t), rh.append(h)
+    got = oracle.attn_prefill_rows(kp, vp, q, cuq, ctx, bt, 0.4, rs, rt, rh)
+    assert any(h // G != h % Hkv for h in rh)
+    for i, (s, t, h) in enumerate(zip(rs, rt, rh)):
+        assert np.array_equal(got[i], full[cuq[s] + t, h])
+        # independent of both drivers: dense softmax over the contiguous K/V of KV head h // G
+        p = int(ctx[s]) + t
+        kk, vv = f64(ks[s])[: p + 1, h // G], f64(vs[s])[: p + 1, h // G]
+        sc = 0.4 * kk @ f64(q[cuq[s] + t, h])
+        w = np.exp(sc - sc.max())
+        assert np.abs(got[i] - (w / w.sum()) @ vv).max() <= 1e-12
+
+
 def test_zero_length_sequences_are_noops(oracle):
     rng = rng_for("zero")
     kp, vp, bt, ks, vs, cu = paged_setup(oracle, rng, [20, 0, 5], 1, 8)
