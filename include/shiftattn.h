@@ -2,11 +2,11 @@
  * shiftattn — C ABI of the Shift Parallelism attention hot path on one MI355X (gfx950).
  *
  * The operation is causal grouped-query attention over ONE GPU's head shard, reading a
- * paged KV cache whose layout is the same in the sequence-parallel (Ulysses) prefill mode
- * and the tensor-parallel decode mode.  Source: the paper's section "Introducing Shift
- * Parallelism" — the KV-cache layout does not change between SP and TP as long as
- * SP x TP = P, and in both modes each GPU computes the same subset of attention heads over
- * all tokens (Figure 2).  That invariance is structural here: sp_kv_append,
+ * paged KV cache.  Source: the paper's section "Introducing Shift Parallelism" and Figure 2.
+ * Two facts stated there shape this interface: switching between the sequence-parallel
+ * (Ulysses) mode and the tensor-parallel mode leaves the KV cache where it is whenever the
+ * two degrees multiply to the size of the GPU group, and under either mode a GPU attends
+ * with the same subset of heads over every token.  Both are structural here: sp_kv_append,
  * sp_attn_prefill and sp_attn_decode take the same sp_cache_desc and block table, and the
  * ABI has no re-layout entry point.
  *
@@ -16,11 +16,15 @@
  *   - bf16 tensors are raw 16-bit patterns; index arrays are int32.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work: no allocation, no synchronisation, no host<->device copies.
- *   - The caller owns every buffer; the library keeps no device state between calls.
+ *   - The caller owns every buffer; the library keeps no device state between calls.  Host
+ *     state: the calling thread's last error text and its sp_debug_set_tuning overrides, both
+ *     thread-local.
  *   - Return value: SP_OK (0) or a negative sp_status.  On any error nothing is launched.
  *     No exception crosses the ABI.  Device-side metadata (lengths, block-table entries)
- *     is NOT validated by the three hot calls; sp_debug_validate_metadata does that,
- *     synchronously, for tests.
+ *     is NOT validated by the hot calls; sp_debug_validate_metadata and
+ *     sp_debug_validate_hints do that, synchronously, for tests.  With bad metadata the hot
+ *     calls stay inside the pools (page ids are clamped for loads; stores to pages outside the
+ *     pool or past the block-table row are skipped) and return unspecified finite-or-not values.
  *   - Page indexing (exact int32 arithmetic): token j of sequence s lives in physical page
  *     block_table[s * max_pages_per_seq + j / 16], row j % 16.
  *   - GQA map: query head h reads KV head h / (num_q_heads / num_kv_heads).
@@ -61,14 +65,18 @@ typedef struct sp_cache_desc {
 
 /*
  * sp_kv_append — write the new tokens' K and V into their pages (the step in front of both
- * attention calls; it is what keeps one cache image valid for both modes).
+ * attention calls).  Paper, section "Introducing Shift Parallelism", the paragraph on the
+ * invariant KV-cache layout: one cache image serves both modes, so there is one append.
  *   k_new, v_new    bf16 [total_new_tokens][num_kv_heads][head_dim], packed by sequence
  *   cu_seqlens_new  int32 [batch + 1] prefix sums of new tokens per sequence
  *   ctx_lens        int32 [batch] tokens already cached per sequence; new token i of
  *                   sequence s goes to absolute position ctx_lens[s] + i
  *   block_table     int32 [batch][max_pages_per_seq]
  * Sequences with zero new tokens are no-ops.  batch == 0 or total_new_tokens == 0 returns
- * SP_OK without launching.  Slots not named by the inputs are left untouched.
+ * SP_OK without launching.  Slots not named by the inputs are left untouched; rows whose page
+ * id lies outside the pool or past the block-table row are skipped.
+ * Sub-ranges: as for sp_attn_prefill (keep k_new, v_new and total_new_tokens, advance the three
+ * index arrays); tokens outside [cu_seqlens_new[0], cu_seqlens_new[batch]) are not touched.
  */
 int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_new,
                  const int32_t *cu_seqlens_new, const int32_t *ctx_lens,
@@ -78,6 +86,8 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
 /*
  * sp_attn_prefill — causal GQA attention for a packed varlen batch of query chunks (the SP
  * mode after the sequence->head all-to-all, and chunked prefill against a cached prefix).
+ * Paper, section "Introducing Shift Parallelism" and Figure 2: in the sequence-parallel mode a
+ * GPU attends with its own heads over all tokens of the request, reading the shared cache.
  *   q, out          bf16 [total_q_tokens][num_q_heads][head_dim]; out is written with one
  *                   round-to-nearest-even from fp32
  *   cu_seqlens_q    int32 [batch + 1]
@@ -85,7 +95,11 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  *                   already have been appended (query i of sequence s is at ctx_lens[s] + i)
  *   max_q_len       host hint: >= the longest chunk in the batch (sizes the grid)
  *   max_kv_len      host hint: >= the largest ctx_lens[s] + chunk length (sizes launches and
- *                   the workspace; keys beyond it may be ignored)
+ *                   the workspace)
+ *                   A hint that is too SMALL is not detected by the call: query rows beyond
+ *                   max_q_len are then not computed (their `out` rows keep their old bytes)
+ *                   and keys beyond max_kv_len may be ignored.  sp_debug_validate_hints checks
+ *                   both hints and total_q_tokens against the device arrays.
  *   scale           softmax scale, normally 1/sqrt(head_dim)
  *   causal          must be 1
  *   workspace       optional device scratch (contents need no initialisation).  With at least
@@ -103,12 +117,14 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  * may be attended in several calls on sub-ranges of its sequences: keep q, out and
  * total_q_tokens, advance cu_seqlens_q, ctx_lens and block_table to the first sequence of the
  * range and pass the range's batch size and hints (cu_seqlens_q keeps its absolute token
- * offsets).  A mixed batch — single-token sequences plus prefill chunks in one step — is best
- * served that way, the short sequences in one call and the chunks in another (or
- * sp_attn_decode for the former): each part then gets the kernel and the launch shape that suit
- * it (measured on 63 decode sequences + one 2048-token chunk: 67 us in two calls, 110 us in
- * one).
- * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax.
+ * offsets).
+ * A mixed batch — single-token sequences plus prefill chunks in one step — is best served
+ * that way, the short sequences in one call and the chunks in another (or sp_attn_decode for
+ * the former): each part then gets the kernel and the launch shape that suit it.
+ * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax.  The error bound of
+ * 1e-2 absolute against the exact result holds for inputs distributed like N(0,1) q, k, v with
+ * scale 1/sqrt(head_dim); it scales with |out| (bf16 output: half an ulp is 2^-9 |out|) and,
+ * for nearly one-hot softmax rows, with the bf16 rounding of the dominant weight (2^-8 |out|).
  */
 int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
                     const int32_t *cu_seqlens_q, const int32_t *ctx_lens,
@@ -119,7 +135,9 @@ int sp_attn_prefill(const sp_cache_desc *cache, const void *q, void *out,
 
 /*
  * sp_attn_decode — one query token per sequence (the TP mode), split over the key range
- * with a log-sum-exp combine pass.
+ * with a log-sum-exp combine pass.  Paper, section "Introducing Shift Parallelism" and
+ * Figure 2: in the tensor-parallel mode the same GPU attends with the same heads, reading the
+ * same cache the prefill mode filled.
  *   q, out          bf16 [batch][num_q_heads][head_dim]
  *   seq_lens        int32 [batch] INCLUDING the current token, whose K/V is already cached;
  *                   a sequence with seq_lens[s] == 0 gets an all-zero output row
@@ -211,8 +229,26 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
                                int32_t max_pages_per_seq);
 
 /*
- * sp_debug_set_tuning — process-wide override of an internal launch parameter, for tuning
- * sweeps and tests.  Not thread-safe against concurrent attention calls.  Keys:
+ * sp_debug_validate_hints — SYNCHRONOUS test helper: copies the length arrays to the host and
+ * checks the host-side hints of an attention call against them.
+ *   cu_seqlens      int32 [batch + 1] (device) of sp_kv_append / sp_attn_prefill / sp_chunk_step,
+ *                   or NULL for sp_attn_decode / sp_decode_step
+ *   lens            int32 [batch] (device): ctx_lens when cu_seqlens is given, else seq_lens
+ *   total_tokens    the call's total_q_tokens / total_new_tokens (ignored without cu_seqlens)
+ *   max_q_len       the call's max_q_len (ignored without cu_seqlens)
+ *   max_len         the call's max_kv_len, or max_seq_len for the decode calls
+ * Checks: lengths non-negative; cu_seqlens non-decreasing with 0 <= cu_seqlens[0] and
+ * cu_seqlens[batch] <= total_tokens; every chunk <= max_q_len; every lens[s] + chunk (or
+ * seq_lens[s]) <= max_len.  Returns SP_OK or SP_ERR_BAD_SHAPE with the first violation in
+ * sp_last_error().
+ */
+int sp_debug_validate_hints(const int32_t *cu_seqlens, const int32_t *lens, int32_t batch,
+                            int32_t total_tokens, int32_t max_q_len, int32_t max_len);
+
+/*
+ * sp_debug_set_tuning — override of an internal launch parameter for the CALLING THREAD (the
+ * workspace-size helpers and the attention calls made by that thread see it; other threads keep
+ * their own values), for tuning sweeps and tests.  Keys:
  *   "decode_chunk"  keys per decode split: 0 (built-in heuristic) or a multiple of 32 in
  *                   [128, 1024].  Changes what sp_attn_decode_workspace_size returns.
  *   "decode_ring"   32-key blocks a decode wave keeps in its LDS ring (one computed on, the
@@ -227,7 +263,8 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  *   "prefill_split" how a prefill workgroup's two wave groups divide the work: 0 (built-in
  *                   heuristic on the grid size), 1 (neighbouring query columns, shared key
  *                   tiles), 2 (same query columns, alternate key tiles, merged at the end).
- *                   Both give the same result up to fp32 summation order.
+ *                   Both give the same result up to fp32 summation order.  Launches that cut
+ *                   key ranges into pieces always take form 2.
  *   "prefill_order" which work item (sequence, query tile) a prefill workgroup takes: 0 (built-in
  *                   choice), 1 (by launch index: last query tiles of all sequences first), 2 (the
  *                   workgroup with the r-th launch index takes the r-th heaviest item; batches of
@@ -238,28 +275,6 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
  * Returns SP_OK, SP_ERR_NULL or SP_ERR_UNSUPPORTED (unknown key / value out of range).
  */
 int sp_debug_set_tuning(const char *key, int32_t value);
-
-/*
- * sp_debug_ceiling_mfma / sp_debug_ceiling_stream — measurement aids, not part of the hot path:
- * the two reference kernels a benchmark times to see what THIS chip delivers for the resources
- * the attention kernels are bound by (the published peaks assume the full boost clock).
- *   mfma    a register-resident bf16 32x32x16 MFMA loop on every CU: 8 waves per CU, `iters`
- *           (even) rounds of four MFMAs each.  random_operands == 0 multiplies the same two
- *           operand registers over and over; != 0 cycles through eight A and eight B registers
- *           of pseudo-random values, as a kernel working on real data does (more power, hence
- *           a lower sustained clock).  *host_flops (host pointer) receives the number of flops
- *           the launch performs.  `sink` is device scratch of at least 16 + 4 * CUs bytes;
- *           after the launch its first two uint64 hold the shader-clock cycles and the ticks of
- *           the constant 100 MHz counter that workgroup 0 spent in the loop (their ratio is the
- *           clock the chip sustained under that load).
- *   stream  reads `bytes` (a multiple of 16) from device buffer `buf` once, 16 bytes per lane,
- *           nontemporal; `sink` is device scratch of at least 32 * CUs bytes.
- * Both only enqueue on `stream`; the caller times them.
- */
-int sp_debug_ceiling_mfma(int32_t iters, int32_t random_operands, double *host_flops, void *sink,
-                          size_t sink_bytes, void *stream);
-int sp_debug_ceiling_stream(const void *buf, size_t bytes, void *sink, size_t sink_bytes,
-                            void *stream);
 
 const char *sp_status_string(int status); /* static string                              */
 const char *sp_last_error(void);          /* thread-local detail of the last failure    */

@@ -14,6 +14,10 @@ from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshiftattn.so")
+if os.environ.get("SP_LIB_SANITIZE", "") == "1":
+    # the copy whose host code carries ASan + UBSan instrumentation (CPU-only boundary tests; the
+    # process must run with the matching sanitizer runtime preloaded)
+    LIB_PATH = os.path.join(_HERE, "_build", "san", "libshiftattn_san.so")
 
 SP_OK = 0
 SP_ERR_NULL = -1
@@ -25,9 +29,8 @@ SP_ERR_HIP = -5
 EXPORTS = (
     "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_decode_step", "sp_chunk_step", "sp_ulysses_pack", "sp_ulysses_unpack",
     "sp_attn_prefill_workspace_size",
-    "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_set_tuning",
-    "sp_debug_ceiling_mfma", "sp_debug_ceiling_stream", "sp_status_string",
-    "sp_last_error", "sp_version",
+    "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_validate_hints", "sp_debug_set_tuning",
+    "sp_status_string", "sp_last_error", "sp_version",
 )
 
 
@@ -87,10 +90,8 @@ def lib() -> ctypes.CDLL:
         L.sp_debug_validate_metadata.restype = ctypes.c_int
         L.sp_debug_set_tuning.argtypes = [ctypes.c_char_p, i32]
         L.sp_debug_set_tuning.restype = ctypes.c_int
-        L.sp_debug_ceiling_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
-        L.sp_debug_ceiling_mfma.restype = ctypes.c_int
-        L.sp_debug_ceiling_stream.argtypes = [vp, sz, vp, sz, vp]
-        L.sp_debug_ceiling_stream.restype = ctypes.c_int
+        L.sp_debug_validate_hints.argtypes = [vp, vp, i32, i32, i32, i32]
+        L.sp_debug_validate_hints.restype = ctypes.c_int
         L.sp_status_string.argtypes = [ctypes.c_int]
         L.sp_status_string.restype = ctypes.c_char_p
         L.sp_last_error.restype = ctypes.c_char_p
@@ -233,20 +234,11 @@ def sp_debug_set_tuning(key: str, value: int) -> None:
     _check(lib().sp_debug_set_tuning(key.encode(), int(value)))
 
 
-def sp_debug_ceiling_mfma(iters: int, sink, random_operands: bool = False, stream=None) -> float:
-    """Enqueues the MFMA-only reference loop; returns the flops it performs.  `sink`: cuda uint8 tensor."""
-    flops = ctypes.c_double(0.0)
-    _check(lib().sp_debug_ceiling_mfma(int(iters), int(bool(random_operands)), ctypes.byref(flops), _ptr(sink),
-                                       sink.numel() * sink.element_size(), _stream(stream)))
-    return flops.value
-
-
-def sp_debug_ceiling_stream(buf, sink, stream=None) -> int:
-    """Enqueues the streaming-read reference kernel over all of `buf`; returns the bytes it reads."""
-    nbytes = buf.numel() * buf.element_size()
-    _check(lib().sp_debug_ceiling_stream(_ptr(buf), nbytes, _ptr(sink), sink.numel() * sink.element_size(),
-                                         _stream(stream)))
-    return nbytes
+def sp_debug_validate_hints(cu_seqlens, lens, total_tokens: int, max_q_len: int, max_len: int) -> None:
+    """Synchronous check of an attention call's host-side hints against its device length arrays
+    (cu_seqlens None: a decode call, lens = seq_lens)."""
+    _check(lib().sp_debug_validate_hints(_ptr(cu_seqlens), _ptr(lens), lens.shape[0], int(total_tokens),
+                                         int(max_q_len), int(max_len)))
 
 
 def sp_ulysses_pack(x, send, world: int, stream=None) -> None:

@@ -1,10 +1,31 @@
 // Two reference kernels that measure what this chip delivers for the two resources the attention
 // kernels are bound by, so that achieved figures can be read against the box as well as against
 // the datasheet: a register-resident bf16 MFMA loop (no memory, no LDS, no VALU work) and a
-// plain 16-byte-per-lane streaming read.  Measurement aids only; nothing on the hot path uses them.
-#include "sp_common.h"
+// plain 16-byte-per-lane streaming read.  Measurement aids only, built into their own shared
+// object (libspceilings.so, declared in include/sp_ceilings.h): the attention library neither
+// contains nor uses them.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace sp {
+#include <cstdarg>
+#include <cstdio>
+
+#include "sp_ceilings.h"
+
+namespace spc {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+static thread_local char g_err[256] = "";
+static int fail(int status, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return status;
+}
 
 // 8 waves per workgroup, each with four independent 32x32x16 accumulators.  RANDOM = false
 // multiplies the same two operand registers over and over (what a peak-rate loop usually does);
@@ -59,14 +80,17 @@ __global__ __launch_bounds__(512) void ceiling_mfma_kernel(int iters, float *sin
   }
 }
 
+template <int UNROLL>
 __global__ __launch_bounds__(256) void ceiling_stream_kernel(const u32x4 *__restrict__ src, size_t n16, uint32_t *sink) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   u32x4 x = {0, 0, 0, 0};
-  for (; i + 3 * stride < n16; i += 4 * stride) {  // four independent loads in flight per lane
-    u32x4 v0 = __builtin_nontemporal_load(src + i), v1 = __builtin_nontemporal_load(src + i + stride);
-    u32x4 v2 = __builtin_nontemporal_load(src + i + 2 * stride), v3 = __builtin_nontemporal_load(src + i + 3 * stride);
-    x ^= v0 ^ v1 ^ v2 ^ v3;
+  for (; i + (UNROLL - 1) * stride < n16; i += UNROLL * stride) {  // UNROLL independent loads in flight per lane
+    u32x4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) x ^= v[u];
   }
   for (; i < n16; i += stride) x ^= __builtin_nontemporal_load(src + i);
   const uint32_t r = x[0] ^ x[1] ^ x[2] ^ x[3];
@@ -84,20 +108,20 @@ static int cu_count() {
   return n;
 }
 
-}  // namespace sp
+}  // namespace spc
 
-using namespace sp;
+using namespace spc;
 
 extern "C" {
 
-int sp_debug_ceiling_mfma(int32_t iters, int32_t random_operands, double *host_flops, void *sink,
+int spc_ceiling_mfma(int32_t iters, int32_t random_operands, double *host_flops, void *sink,
                           size_t sink_bytes, void *stream) {
-  if (!host_flops || !sink) return fail(SP_ERR_NULL, "sp_debug_ceiling_mfma: NULL argument");
-  if (iters <= 0 || iters % 2 != 0) return fail(SP_ERR_BAD_SHAPE, "iters=%d must be positive and even", iters);
+  if (!host_flops || !sink) return fail(-1, "spc_ceiling_mfma: NULL argument");
+  if (iters <= 0 || iters % 2 != 0) return fail(-2, "iters=%d must be positive and even", iters);
   const int cus = cu_count();
-  if (cus <= 0) return fail(SP_ERR_HIP, "cannot read the device properties");
+  if (cus <= 0) return fail(-5, "cannot read the device properties");
   const size_t need = (size_t)cus * sizeof(float) + 16;
-  if (sink_bytes < need) return fail(SP_ERR_WORKSPACE, "sink: need %zu bytes, got %zu", need, sink_bytes);
+  if (sink_bytes < need) return fail(-4, "sink: need %zu bytes, got %zu", need, sink_bytes);
   // layout of sink: two 64-bit clock readings, then one float per workgroup
   if (random_operands)
     hipLaunchKernelGGL(ceiling_mfma_kernel<true>, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters,
@@ -106,23 +130,32 @@ int sp_debug_ceiling_mfma(int32_t iters, int32_t random_operands, double *host_f
     hipLaunchKernelGGL(ceiling_mfma_kernel<false>, dim3(cus), dim3(512), 0, (hipStream_t)stream, iters,
                        (float *)((char *)sink + 16), (unsigned long long *)sink);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(SP_ERR_HIP, "ceiling launch: %s", hipGetErrorString(e));
+  if (e != hipSuccess) return fail(-5, "ceiling launch: %s", hipGetErrorString(e));
   *host_flops = (double)cus * 8.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
-  return SP_OK;
+  return 0;
 }
 
-int sp_debug_ceiling_stream(const void *buf, size_t bytes, void *sink, size_t sink_bytes, void *stream) {
-  if (!buf || !sink) return fail(SP_ERR_NULL, "sp_debug_ceiling_stream: NULL argument");
-  if (bytes < 16 || bytes % 16 != 0) return fail(SP_ERR_BAD_SHAPE, "bytes=%zu must be a positive multiple of 16", bytes);
+int spc_ceiling_stream(const void *buf, size_t bytes, int32_t blocks_per_cu, int32_t unroll, void *sink,
+                       size_t sink_bytes, void *stream) {
+  if (!buf || !sink) return fail(-1, "spc_ceiling_stream: NULL argument");
+  if (bytes < 16 || bytes % 16 != 0) return fail(-2, "bytes=%zu must be a positive multiple of 16", bytes);
+  if (blocks_per_cu < 1 || blocks_per_cu > 32 || (unroll != 4 && unroll != 8))
+    return fail(-2, "blocks_per_cu=%d (1..32), unroll=%d (4 or 8)", blocks_per_cu, unroll);
   const int cus = cu_count();
-  if (cus <= 0) return fail(SP_ERR_HIP, "cannot read the device properties");
-  const int grid = cus * 8;
-  if (sink_bytes < (size_t)grid * 4) return fail(SP_ERR_WORKSPACE, "sink: need %zu bytes, got %zu", (size_t)grid * 4, sink_bytes);
-  hipLaunchKernelGGL(ceiling_stream_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)buf,
-                     bytes / 16, (uint32_t *)sink);
+  if (cus <= 0) return fail(-5, "cannot read the device properties");
+  const int grid = cus * blocks_per_cu;
+  if (sink_bytes < (size_t)grid * 4) return fail(-4, "sink: need %zu bytes, got %zu", (size_t)grid * 4, sink_bytes);
+  if (unroll == 4)
+    hipLaunchKernelGGL(ceiling_stream_kernel<4>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)buf,
+                       bytes / 16, (uint32_t *)sink);
+  else
+    hipLaunchKernelGGL(ceiling_stream_kernel<8>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)buf,
+                       bytes / 16, (uint32_t *)sink);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(SP_ERR_HIP, "ceiling launch: %s", hipGetErrorString(e));
-  return SP_OK;
+  if (e != hipSuccess) return fail(-5, "ceiling launch: %s", hipGetErrorString(e));
+  return 0;
 }
+
+const char *spc_last_error(void) { return g_err; }
 
 }  // extern "C"

@@ -1,5 +1,10 @@
-"""Build step for libshiftattn.so: every HIP source under csrc/ compiled for gfx950 with hipcc
-and linked into one shared library next to this file (in-tree, so it travels with the repo)."""
+"""Build step: every HIP source under csrc/ compiled for gfx950 with hipcc and linked into
+libshiftattn.so next to this file (in-tree, so it travels with the repo); the benchmark's
+reference kernels under bench_kernels/ go into a shared object of their own, libspceilings.so.
+
+``python -m paper_2507_11830_amd.build --sanitize-host`` builds a second copy of libshiftattn
+whose HOST code is instrumented with AddressSanitizer + UndefinedBehaviorSanitizer
+(_build/san/libshiftattn_san.so; device code is unchanged) for the CPU-only boundary tests."""
 from __future__ import annotations
 
 import glob
@@ -13,7 +18,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
+BENCH_SRC = os.path.join(HERE, "bench_kernels")
 LIB = os.path.join(HERE, "libshiftattn.so")
+CEIL_LIB = os.path.join(HERE, "libspceilings.so")
+SAN_LIB = os.path.join(OBJ_DIR, "san", "libshiftattn_san.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -22,6 +30,9 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
+# host-side instrumentation only: each -fsanitize= goes directly behind -Xarch_host
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
 
 
 def _check_m0(src: str, asm: str) -> None:
@@ -43,37 +54,64 @@ def _check_m0(src: str, asm: str) -> None:
                            + "\n".join(bad[:10]))
 
 
-def _compile(src: str) -> str:
+def _compile(src: str, obj_dir: str = OBJ_DIR, extra_flags=()) -> str:
     base = os.path.basename(src).replace(".hip", "")
-    obj = os.path.join(OBJ_DIR, base + ".o")
+    obj = os.path.join(obj_dir, base + ".o")
     with open(src) as f:
         uses_lds_dma = "global_load_lds" in f.read()
     extra = ["-save-temps=obj"] if uses_lds_dma else []
-    r = subprocess.run([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, *FLAGS, *extra_flags, *extra, "-c", src, "-o", obj], capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
         raise RuntimeError(f"hipcc failed on {src}")
     if uses_lds_dma:
-        _check_m0(src, os.path.join(OBJ_DIR, base + "-hip-amdgcn-amd-amdhsa-gfx950.s"))
+        asm = os.path.join(obj_dir, base + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+        if not os.path.exists(asm):
+            raise RuntimeError(f"{os.path.basename(src)}: the compiler left no {asm}; the M0 check cannot run, "
+                               "so the build is refused")
+        _check_m0(src, asm)
     return obj
+
+
+def _link(objs, lib: str, extra_flags=()) -> None:
+    tmp = lib + f".tmp{os.getpid()}"
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *extra_flags, "-o", tmp, *objs],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError(f"link of {lib} failed")
+    os.replace(tmp, lib)
 
 
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(_compile, srcs))
-    tmp = LIB + f".tmp{os.getpid()}"
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        sys.stderr.write(r.stdout + r.stderr)
-        raise RuntimeError("link failed")
-    os.replace(tmp, LIB)
+    bench = sorted(glob.glob(os.path.join(BENCH_SRC, "*.hip")))
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs) + len(bench))) as ex:
+        objs = list(ex.map(_compile, srcs + bench))
+    _link(objs[:len(srcs)], LIB)
+    _link(objs[len(srcs):], CEIL_LIB)
     if verbose:
         print("built", LIB)
+        print("built", CEIL_LIB)
     return LIB
 
 
+def build_sanitized(verbose: bool = False) -> str:
+    """libshiftattn with ASan + UBSan on the host side (argument validation, launch set-up)."""
+    out_dir = os.path.dirname(SAN_LIB)
+    os.makedirs(out_dir, exist_ok=True)
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+        objs = list(ex.map(lambda s_: _compile(s_, out_dir, SAN_FLAGS), srcs))
+    _link(objs, SAN_LIB, ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"])
+    if verbose:
+        print("built", SAN_LIB)
+    return SAN_LIB
+
+
 if __name__ == "__main__":
-    build(verbose=True)
+    if "--sanitize-host" in sys.argv:
+        build_sanitized(verbose=True)
+    else:
+        build(verbose=True)

@@ -212,6 +212,35 @@ int sp_debug_validate_metadata(const sp_cache_desc *cache, const int32_t *seq_le
   return SP_OK;
 }
 
+int sp_debug_validate_hints(const int32_t *cu_seqlens, const int32_t *lens, int32_t batch, int32_t total_tokens,
+                            int32_t max_q_len, int32_t max_len) {
+  if (batch < 0) return fail(SP_ERR_BAD_SHAPE, "negative batch");
+  if (batch == 0) return SP_OK;
+  if (!lens) return fail(SP_ERR_NULL, "NULL length array");
+  std::vector<int32_t> ln(batch), cu(cu_seqlens ? batch + 1 : 0);
+  hipError_t e = hipMemcpy(ln.data(), lens, ln.size() * 4, hipMemcpyDeviceToHost);
+  if (e == hipSuccess && cu_seqlens) e = hipMemcpy(cu.data(), cu_seqlens, cu.size() * 4, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail(SP_ERR_HIP, "hipMemcpy: %s", hipGetErrorString(e));
+  if (cu_seqlens) {
+    if (cu[0] < 0) return fail(SP_ERR_BAD_SHAPE, "cu_seqlens[0]=%d is negative", cu[0]);
+    if (cu[batch] > total_tokens)
+      return fail(SP_ERR_BAD_SHAPE, "cu_seqlens[%d]=%d exceeds total_tokens=%d", batch, cu[batch], total_tokens);
+  }
+  for (int s = 0; s < batch; ++s) {
+    if (ln[s] < 0) return fail(SP_ERR_BAD_SHAPE, "lens[%d]=%d is negative", s, ln[s]);
+    long reach = ln[s];
+    if (cu_seqlens) {
+      const long n = (long)cu[s + 1] - cu[s];
+      if (n < 0) return fail(SP_ERR_BAD_SHAPE, "cu_seqlens decreases at sequence %d (%d -> %d)", s, cu[s], cu[s + 1]);
+      if (n > max_q_len) return fail(SP_ERR_BAD_SHAPE, "sequence %d has %ld tokens > max_q_len=%d", s, n, max_q_len);
+      reach += n;
+    }
+    if (reach > max_len)
+      return fail(SP_ERR_BAD_SHAPE, "sequence %d reaches %ld keys > the length hint %d", s, reach, max_len);
+  }
+  return SP_OK;
+}
+
 int sp_debug_set_tuning(const char *key, int32_t value) {
   if (!key) return fail(SP_ERR_NULL, "tuning key is NULL");
   if (!strcmp(key, "decode_chunk")) {

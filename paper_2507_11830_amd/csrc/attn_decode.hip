@@ -37,8 +37,8 @@ struct DecodeArgs {
   float tau;  // lazy-rescale threshold in raw score units (8 / sl2e)
 };
 
-static int g_chunk_override = 0;  // tuning hooks (sp_debug_set_tuning), 0 = heuristic
-static int g_ring_override = 0;
+static thread_local int g_chunk_override = 0;  // tuning hooks of the calling thread (sp_debug_set_tuning), 0 = heuristic
+static thread_local int g_ring_override = 0;
 
 static int pick_chunk(int batch, int num_q_heads, int max_seq_len, int q_len = 1) {
   if (g_chunk_override > 0) return g_chunk_override;
@@ -216,7 +216,12 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
   }
   const int kv1 = min(kv_end, kv0 + a.chunk);
   const int nb = (kv1 - kv0 + 31) >> 5;  // blocks of this wave, >= 1
-  my_page = min(max(my_page, 0), a.num_pages - 1);  // bad metadata must not become a wild load
+  // Bad metadata must not become a wild access: loads go through the clamped page id (finite
+  // garbage, as sp_attn_decode documents for unvalidated metadata), the fused-append stores
+  // through the raw one, and are skipped when it lies outside the pool or past the table row
+  // (the same rows sp_kv_append skips).
+  const int my_page_raw = (kv0 >> 4) + lane < a.max_pages ? my_page : -1;
+  my_page = min(max(my_page, 0), a.num_pages - 1);
 
   // ---- block loads.  Instruction j of a matrix covers RPI rows: lane l fills chunk slot l % 16
   // of line 4j + l / 16 of the block and fetches whichever global chunk the swizzle assigns to
@@ -348,7 +353,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
         const int pos = base + row;
         // page of this position, from the lane that holds it: taken by all lanes, outside the
         // branch (a cross-lane read must not depend on which lanes the branch leaves active)
-        const int pg = __shfl(my_page, min((pos - kv0) >> 4, 63));
+        const int pg = __shfl(my_page_raw, min((pos - kv0) >> 4, 63));
         if (pos >= ctx) {
           const int t = min(pos, L - 1) - ctx;
           const size_t noff = (((size_t)(tok0 + t) * a.Hkv + kvh) * CPR + c) * 16;
@@ -356,7 +361,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
           const u32x4 vn = *reinterpret_cast<const u32x4 *>(a.v_new + noff);
           *(lds_u32x4 *)(const_cast<lds_char *>(sbk) + Z::template offset<false>(row, c)) = kn;
           *(lds_u32x4 *)(const_cast<lds_char *>(sbv) + Z::template offset<true>(row, c)) = vn;
-          if (writer && pos < kv1) {
+          if (writer && pos < kv1 && pg >= 0 && pg < a.num_pages) {
             const size_t dst = (size_t)(unsigned)pg * page_stride + (size_t)(pos & 15) * ROWB + c * 16;
             *reinterpret_cast<u32x4 *>(const_cast<char *>(kpool) + dst) = kn;
             *reinterpret_cast<u32x4 *>(const_cast<char *>(vpool) + dst) = vn;
@@ -379,8 +384,8 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
           *(lds_u32x4 *)(const_cast<lds_char *>(sbv) + Z::template offset<true>(row, c)) = vnew;
         }
       }
-      if (lane < CPR && head0 % a.group == 0) {  // one writer per (sequence, KV head)
-        const int pg = __builtin_amdgcn_readlane(my_page, last_row >> 4);
+      const int pg = __builtin_amdgcn_readlane(my_page_raw, last_row >> 4);
+      if (lane < CPR && head0 % a.group == 0 && pg >= 0 && pg < a.num_pages) {  // one writer per (sequence, KV head)
         const size_t dst = (size_t)(unsigned)pg * page_stride + (size_t)((kv0 + last_row) & 15) * ROWB + c * 16;
         *reinterpret_cast<u32x4 *>(const_cast<char *>(kpool) + dst) = knew;
         *reinterpret_cast<u32x4 *>(const_cast<char *>(vpool) + dst) = vnew;
@@ -630,7 +635,7 @@ __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ p
         __builtin_convertvector(M == -INFINITY ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[p] * inv, bf16x4);
 }
 
-static int g_combine_rows_per_wave = 0;  // tuning hook: 0 heuristic, 1 one slice per wave, 2 whole rows
+static thread_local int g_combine_rows_per_wave = 0;  // tuning hook: 0 heuristic, 1 one slice per wave, 2 whole rows
 void set_combine_form(int form) { g_combine_rows_per_wave = form; }
 
 int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,

@@ -679,10 +679,11 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   }
 }
 
-static int g_split_mode = 0;
-static int g_kv_splits = 0;
-static int g_short_chunk_mode = 0;
-static int g_order_mode = 0;
+// Launch-shape overrides of the calling thread (sp_debug_set_tuning); 0 = built-in heuristic.
+static thread_local int g_split_mode = 0;
+static thread_local int g_kv_splits = 0;
+static thread_local int g_short_chunk_mode = 0;
+static thread_local int g_order_mode = 0;
 void set_prefill_order(int mode) { g_order_mode = mode; }
 void set_prefill_short_chunk(int mode) { g_short_chunk_mode = mode; }
 void set_prefill_split(int mode) { g_split_mode = mode; }
@@ -746,13 +747,13 @@ template <int D>
 static int launch_prefill_d(const PrefillArgs &a, bool split, int batch, int max_q_len, hipStream_t stream) {
   constexpr int KVT = 64, PFD = 4;
   constexpr size_t smem = 4 * (size_t)KVT * D * 2;  // K[2] V[2], unpadded
-  static bool set[4] = {false, false, false, false};
-  if (a.kv_splits > 1) {
-    if (split) return launch_cfg(prefill_kernel<D, KVT, PFD, true, true>, &set[0], 2 * smem, 128, a, batch, max_q_len, stream);
-    return launch_cfg(prefill_kernel<D, KVT, PFD, false, true>, &set[1], smem, 256, a, batch, max_q_len, stream);
-  }
-  if (split) return launch_cfg(prefill_kernel<D, KVT, PFD, true, false>, &set[2], 2 * smem, 128, a, batch, max_q_len, stream);
-  return launch_cfg(prefill_kernel<D, KVT, PFD, false, false>, &set[3], smem, 256, a, batch, max_q_len, stream);
+  static bool set[3] = {false, false, false};
+  // Key ranges are only cut into pieces on small grids, which take the 128-column form anyway;
+  // the 256-column form with partial outputs is not instantiated (it would not fit the register
+  // budget of two workgroups per CU).
+  if (a.kv_splits > 1) return launch_cfg(prefill_kernel<D, KVT, PFD, true, true>, &set[0], 2 * smem, 128, a, batch, max_q_len, stream);
+  if (split) return launch_cfg(prefill_kernel<D, KVT, PFD, true, false>, &set[1], 2 * smem, 128, a, batch, max_q_len, stream);
+  return launch_cfg(prefill_kernel<D, KVT, PFD, false, false>, &set[2], smem, 256, a, batch, max_q_len, stream);
 }
 
 int launch_chunk_step(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
@@ -848,8 +849,9 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   a.part_o = (float *)workspace;
   a.part_ml = a.part_o + (size_t)rows * kvs * c.head_dim;
 
-  int rc = c.head_dim == 128 ? launch_prefill_d<128>(a, small_grid, batch, max_q_len, stream)
-                             : launch_prefill_d<64>(a, small_grid, batch, max_q_len, stream);
+  const bool split = small_grid || kvs > 1;
+  int rc = c.head_dim == 128 ? launch_prefill_d<128>(a, split, batch, max_q_len, stream)
+                             : launch_prefill_d<64>(a, split, batch, max_q_len, stream);
   if (rc != SP_OK || kvs == 1) return rc;
   return launch_combine(a.part_o, a.part_ml, out, rows, kvs, c.head_dim, stream, cu_q, batch, num_q_heads);
 }

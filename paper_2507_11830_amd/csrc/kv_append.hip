@@ -56,6 +56,10 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
     }
   }
   const int s = lo;
+  // A call on a sub-range of a batch's sequences passes prefix sums that start above 0 and end
+  // below total_new_tokens: tokens outside [cu_new[0], cu_new[batch]) belong to other calls.
+  const int cu_lo = staged ? s_cu[0] : cu_new[0], cu_hi = staged ? s_cu[batch] : cu_new[batch];
+  if (tok < cu_lo || tok >= cu_hi) return;
   const int pos = ctx_lens[s] + (tok - (staged ? s_cu[s] : cu_new[s]));
   const int logical = pos >> 4;
   if (pos < 0 || logical >= max_pages) return;

@@ -119,11 +119,6 @@ class OracleRunner:
             return self.o.attn_prefill(self.kp, self.vp, st.q, st.cu_new, st.ctx_lens, w.block_table, w.scale)
         return self.o.attn_decode(self.kp, self.vp, st.q, st.seq_lens, w.block_table, w.scale)
 
-    def attend_rows(self, st: W.Step, row_seq, row_tok, row_head) -> np.ndarray:
-        w = self.w
-        return self.o.attn_prefill_rows(self.kp, self.vp, st.q, st.cu_new, st.ctx_lens, w.block_table,
-                                        w.scale, row_seq, row_tok, row_head)
-
 
 def report_err(name, got_bits, want):
     got = W.bf16_bits_to_f64(got_bits)
@@ -133,21 +128,3 @@ def report_err(name, got_bits, want):
     print(f"[parity] {name}: max abs err {err.max():.5f} at {idx} (gpu {got[idx]:.5f} oracle {want[idx]:.5f})",
           flush=True)
     return float(err.max())
-
-
-def sample_rows(rng, st: W.Step, Hq: int, n: int):
-    """n random (seq, token-in-chunk, head) triples, always including the first and last rows."""
-    lens = st.new_lens
-    seqs = np.nonzero(lens > 0)[0]
-    rs = rng.choice(seqs, size=n, p=lens[seqs] / lens[seqs].sum())
-    rt = np.array([rng.integers(0, lens[s]) for s in rs])
-    rh = rng.integers(0, Hq, size=n)
-    s_last = seqs[-1]
-    rs[:4] = [seqs[0], seqs[0], s_last, s_last]
-    rt[:4] = [0, min(1, lens[seqs[0]] - 1), lens[s_last] - 1, max(0, lens[s_last] - 2)]
-    return rs.astype(np.int32), rt.astype(np.int32), rh.astype(np.int32)
-
-
-def gather_rows(out_bits, st: W.Step, rs, rt, rh):
-    tok = st.cu_new[rs] + rt
-    return out_bits[tok, rh]

@@ -19,10 +19,10 @@ def built_lib():
     return ctypes.CDLL(sp.LIB_PATH)
 
 
-def header_functions():
-    text = open(os.path.join(ROOT, "include", "shiftattn.h")).read()
+def header_functions(header="shiftattn.h", prefix="sp_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sp_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(%s[a-z_]+)\s*\(" % prefix, text)))
 
 
 def test_header_declares_the_three_hot_calls():
@@ -34,6 +34,23 @@ def test_header_declares_the_three_hot_calls():
 def test_library_exports_every_declared_symbol(built_lib):
     for n in header_functions():
         assert hasattr(built_lib, n), f"{n} declared in shiftattn.h but not exported"
+
+
+def test_bench_only_library_exports_its_header_and_the_product_library_holds_no_bench_kernels(built_lib):
+    """The benchmark's reference kernels live in a shared object of their own."""
+    from paper_2507_11830_amd import ceilings
+
+    names = header_functions("sp_ceilings.h", "spc_")
+    assert names == sorted(ceilings.EXPORTS)
+    L = ctypes.CDLL(ceilings.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in sp_ceilings.h but not exported"
+        assert not hasattr(built_lib, n)
+    assert not any("ceiling" in n for n in header_functions())
+
+
+def test_every_include_header_is_covered():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["shiftattn.h", "sp_ceilings.h"]
 
 
 def test_binding_names_match_header():
@@ -154,6 +171,37 @@ def test_tuning_keys_are_validated(built_lib):
     for key in (b"decode_chunk", b"decode_ring", b"prefill_split", b"prefill_kv_splits", b"prefill_short_chunk",
                 b"prefill_order", b"combine_form"):
         assert L.sp_debug_set_tuning(key, 0) == sp.SP_OK
+
+
+def test_tuning_overrides_are_per_thread(built_lib):
+    """An override set by one thread changes that thread's workspace sizing only."""
+    import threading
+
+    import paper_2507_11830_amd as sp
+
+    f = lambda: sp.sp_attn_decode_workspace_size(64, 8192, 8, 128)
+    base = f()
+    seen = {}
+
+    def other():
+        sp.sp_debug_set_tuning("decode_chunk", 128)
+        seen["other"] = f()
+
+    t = threading.Thread(target=other)
+    t.start()
+    t.join()
+    assert seen["other"] == 64 * 8 * (8192 // 128) * 130 * 4
+    assert f() == base != seen["other"]
+
+
+def test_hint_validation_rejects_bad_arguments_without_a_gpu(built_lib):
+    import paper_2507_11830_amd as sp
+
+    L = sp.lib()
+    one = ctypes.c_void_p(0x4000)
+    assert L.sp_debug_validate_hints(None, None, 0, 0, 0, 0) == sp.SP_OK
+    assert L.sp_debug_validate_hints(None, None, 3, 0, 0, 0) == sp.SP_ERR_NULL
+    assert L.sp_debug_validate_hints(one, one, -1, 0, 0, 0) == sp.SP_ERR_BAD_SHAPE
 
 
 def test_bench_refuses_more_than_one_gpu():
