@@ -10,6 +10,7 @@ from __future__ import annotations
 import glob
 import os
 import re
+import shlex
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -29,6 +30,7 @@ FLAGS = [
     # keep the compiler from forming packed-fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    *shlex.split(os.environ.get("SP_HIPCC_EXTRA", "")),   # extra compiler flags for experiments
 ]
 # host-side instrumentation only: each -fsanitize= goes directly behind -Xarch_host
 SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",

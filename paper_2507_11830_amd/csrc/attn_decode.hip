@@ -471,7 +471,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
         for (int nt = 0; nt < NT; ++nt)
           o[nt][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[nt][ks], o[nt][db], 0, 0, 0);
       }
-    if (L <= 64) {  // very short sequences: weights as hi + lo, so bf16 rounding of P stays out of the tolerance
+    if (L <= 256) {  // short sequences: weights as hi + lo, so the bf16 rounding of P (which only averages out over many keys) stays out of the tolerance
       bf16x8 plo[NT][2];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {

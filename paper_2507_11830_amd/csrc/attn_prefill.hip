@@ -269,11 +269,26 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     q_len = __builtin_amdgcn_readfirstlane(it.q_len);
     ctx = __builtin_amdgcn_readfirstlane(it.ctx);
   } else {
-    const int sh = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
+    int sh, row;
+    if ((gridDim.x & 7) == 0) {
+      // A multiple of 8 (sequence, head group) streams: every XCD gets its own streams with ALL their
+      // query tiles (workgroup ids go round-robin over the XCDs, so XCD x sees the ids = x mod 8),
+      // heaviest tiles first.  The workgroups an XCD runs at any moment then belong to a few
+      // streams and sit at neighbouring query tiles, so they walk the same K/V pages nearly in
+      // step and the XCD's L2 serves most of their tile loads (rotating streams over the XCDs
+      // instead puts about one workgroup per stream on an XCD, and every tile load misses L2).
+      const unsigned lid = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+      const unsigned xcd = lid & 7, p = lid >> 3, spx = gridDim.x >> 3;
+      row = (int)(p / spx);
+      sh = (int)((p - (unsigned)row * spx) * 8 + xcd);
+    } else {
+      sh = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
+      row = (int)(blockIdx.y + gridDim.y * blockIdx.z);
+    }
     seq = sh / a.n_hgroups;
     hg = sh - seq * a.n_hgroups;
-    tile = a.ntiles_x - 1 - (int)blockIdx.y;
-    piece = (int)blockIdx.z;
+    piece = row / (int)gridDim.y;
+    tile = a.ntiles_x - 1 - (row - piece * (int)gridDim.y);
     q0 = a.cu_q[seq];
     q_len = a.cu_q[seq + 1] - q0;
     ctx = a.ctx_lens[seq];
@@ -335,7 +350,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   const int ntl = T - t_begin;
   const int Tl = SPLIT ? (ntl - grp + 1) / 2 : ntl;  // tiles this group computes on
   const int P = SPLIT ? (ntl + 1) / 2 : ntl;         // tile periods (= barriers) of the workgroup
-  auto gtile = [&](int i) { return t_begin + (SPLIT ? 2 * i + grp : i); };  // local tile number -> key tile of the sequence
+  auto gtile = [&](int i) __attribute__((always_inline)) { return t_begin + (SPLIT ? 2 * i + grp : i); };  // local tile number -> key tile of the sequence
 
   // ---- tile loads, all issued by the first group during its MFMA phase (the one phase that
   // starts right after a barrier AND has issue slots to spare; the same instructions placed in
@@ -346,78 +361,102 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // that slot.  Rows past the end of the sequence are redirected to its last valid row (finite
   // data; their weights are masked to zero).  Page ids are wave-uniform and read from the block
   // table one period ahead.
+  // Everything a load needs per lane is computed before the loop: the byte offset inside a
+  // (page, kv head) block per instruction, for K and for V (their swizzles differ).  Only the
+  // page that holds the sequence's last key needs other offsets (rows clamped); a stream reaches
+  // it with its last loads and repeats it from then on, so the offsets are switched once, outside
+  // the MFMA sequences, when that page comes up.  A VALU instruction in a matrix phase is not
+  // free: measured with two waves on a SIMD, the second wave gets about five plain VALU
+  // instructions in per 32-cycle MFMA of the first, and the softmax needs nearly all of them.
   constexpr int NSTREAM = SPLIT ? 2 : 1;  // K/V tile streams of the workgroup
   constexpr int NLD = NSTREAM * 2 * NIW;  // load instructions per wave and period
   const int last_kv = kv_end - 1, last_page = last_kv >> 4;
   const int dq = lane >> 4, dslot = lane & 15;
-  auto stream_tile = [&](int g, int i) { return t_begin + (SPLIT ? 2 * i + g : i); };  // local tile i of stream g
+  auto stream_tile = [&](int g, int i) __attribute__((always_inline)) { return t_begin + (SPLIT ? 2 * i + g : i); };  // local tile i of stream g
+  auto lane_off = [&](bool is_v, int j, int rip_lim) __attribute__((always_inline)) {  // instruction j of a page load: this lane's source offset
+    const int lp = 4 * j + dq;  // line inside the page
+    const int cl = dslot ^ (is_v ? Z::gv(lp) : Z::gk(lp));
+    const int rip = D == 128 ? lp : 2 * lp + (cl >> 3);
+    const int chunk = D == 128 ? cl : (cl & 7);
+    return (unsigned)(min(rip, rip_lim) * ROWB + chunk * 16);
+  };
+  unsigned voff[NSTREAM][2][NIW];  // [stream][K, V][instruction]
+#pragma unroll
+  for (int g = 0; g < NSTREAM; ++g)
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) voff[g][m][j] = lane_off(m != 0, j, 15);
   // The inline assembly below makes the compiler treat every later load as possibly clobbered,
   // so block-table reads are vector loads; the value stays in a VGPR until the load that needs
   // it is issued one period later, and only then moves to an SGPR.
-  auto page_of = [&](int gt) {  // all lanes read the same entry
+  auto page_of = [&](int gt) __attribute__((always_inline)) {  // all lanes read the same entry
     return bt_row[min(min(gt, T - 1) * (KVT / kPage) + wq, last_page)];
   };
   struct TileLoad {   // wave-uniform description of one page-sized load (NIW instructions)
     const char *pb;   // start of the (page, kv head) block in the pool
     unsigned dst0;    // LDS byte address of this wave's part of the tile slot
-    int rip_lim;      // last row of the page that may be read
   };
-  auto dma_prep = [&](bool is_v, int g, int gt, int pg, int slot) {
-    const bool tail = min(gt, T - 1) * (KVT / kPage) + wq >= last_page;  // uniform
+  auto dma_prep = [&](bool is_v, int g, int gt, int pg, int slot) __attribute__((always_inline)) {
+    if (min(gt, T - 1) * (KVT / kPage) + wq >= last_page) {  // uniform: the page with the last key, from now on
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) voff[g][is_v][j] = lane_off(is_v, j, last_kv & 15);
+    }
     const unsigned page = (unsigned)min(max(__builtin_amdgcn_readfirstlane(pg), 0), a.num_pages - 1);  // no wild loads on bad metadata
     TileLoad tl;
     tl.pb = (is_v ? a.v_pages : a.k_pages) + ((size_t)page * a.Hkv + kvh) * (kPage * ROWB);
     tl.dst0 = (unsigned)(g * REGION + (is_v ? 2 : 0) * TBYTES + slot * TBYTES + wq * (NIW * 1024));
-    tl.rip_lim = tail ? (last_kv & 15) : 15;
     return tl;
   };
-  auto dma_emit = [&](bool is_v, const TileLoad &tl, int j) {  // instruction j of the load
-    const int lp = 4 * j + dq;  // line inside the page
-    const int cl = dslot ^ (is_v ? Z::gv(lp) : Z::gk(lp));
-    const int rip = D == 128 ? lp : 2 * lp + (cl >> 3);
-    const int chunk = D == 128 ? cl : (cl & 7);
-    const unsigned voff = (unsigned)(min(rip, tl.rip_lim) * ROWB + chunk * 16);
+  auto dma_emit = [&](const TileLoad &tl, unsigned off, int j) __attribute__((always_inline)) {  // instruction j of the load
     const unsigned dst = tl.dst0 + j * 1024;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff), "s"(tl.pb));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off), "s"(tl.pb));
   };
   using std::false_type;
   using std::integral_constant;
   using std::true_type;
   // The loads of period i, prepared right after the barrier that opens it: for every stream, K
   // of local tile i+1 and V of local tile i go into the slots whose last readers finished
-  // before that barrier.  Past a stream's last tile the loads repeat its last tile into a slot
-  // nobody reads.  The NLD instructions are then emitted one at a time, spread over the MFMA
-  // sequence: issued back to back by four waves at once they queue up at the CU's one texture
-  // address unit, and since a wave issues in order, everything behind them waits too.
+  // before that barrier (K(i+1) into slot (i+1) & 1, V(i) into slot i & 1).  Past a stream's
+  // last tile the loads repeat the sequence's last tile into a slot nobody reads.  The NLD
+  // instructions are then emitted one at a time, spread over the MFMA sequence: issued back to
+  // back by four waves at once they queue up at the CU's one texture address unit, and since a
+  // wave issues in order, everything behind them waits too.
   int pg_k[NSTREAM], pg_v[NSTREAM];  // page ids of the next K and V loads (kept in VGPRs)
   TileLoad ld[NSTREAM][2];
-  auto issue_prep = [&](int i) {
+  auto issue_prep = [&](int i, auto parc) __attribute__((always_inline)) {  // parc: i & 1 as a compile-time constant
+    constexpr int PAR = decltype(parc)::value;
 #pragma unroll
     for (int g = 0; g < NSTREAM; ++g) {
-      ld[g][0] = dma_prep(false, g, stream_tile(g, i + 1), pg_k[g], (i + 1) & 1);
-      ld[g][1] = dma_prep(true, g, stream_tile(g, i), pg_v[g], i & 1);
+      ld[g][0] = dma_prep(false, g, stream_tile(g, i + 1), pg_k[g], 1 - PAR);
+      ld[g][1] = dma_prep(true, g, stream_tile(g, i), pg_v[g], PAR);
       pg_v[g] = pg_k[g];
       pg_k[g] = page_of(stream_tile(g, i + 2));
     }
   };
-  auto issue_emit = [&](int n) {  // n-th instruction of the period, n < NLD: streams and matrices interleaved
+  auto issue_emit = [&](int n) __attribute__((always_inline)) {  // n-th instruction of the period, n < NLD: streams and matrices interleaved
     const int j = n / (2 * NSTREAM), g = (n / 2) % NSTREAM, m = n & 1;
-    dma_emit(m != 0, ld[g][m], j);
+    dma_emit(ld[g][m], voff[g][m][j], j);
   };
-  auto wait_loads = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0) only
+  auto wait_loads = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0) only
 
-  // ---- LDS operand addresses of this lane (bytes from the start of LDS) for the current K slot
-  // and the current V slot; a slot change flips one address bit.
-  int kcur[G::kDSteps], vcur[G::kDBlocks];
+  // ---- LDS operand addresses of this lane: absolute LDS byte addresses for slot 0 of the K and
+  // of the V buffers.  Everything else an operand read adds — the slot (TBYTES), the 32-key block
+  // and the 16-key step — is a compile-time constant that goes into the instruction's offset
+  // field, so the matrix phases contain no address arithmetic at all; the tile loop is unrolled
+  // by two for that, one copy per slot parity.
+  const unsigned lds0 = (unsigned)(size_t)smem + (unsigned)rb;
+  unsigned kadr[G::kDSteps], vadr[G::kDBlocks];
 #pragma unroll
-  for (int s = 0; s < G::kDSteps; ++s) kcur[s] = rb + Z::template offset<false>(col, 2 * s + half);
+  for (int s = 0; s < G::kDSteps; ++s) kadr[s] = lds0 + Z::template offset<false>(col, 2 * s + half);
   {
     const int n = lane & 15, dg = (lane >> 4) & 1;
 #pragma unroll
     for (int db = 0; db < G::kDBlocks; ++db)
-      vcur[db] = rb + 2 * TBYTES + Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) +
+      vadr[db] = lds0 + 2 * TBYTES + Z::template offset<true>(4 * half + (n >> 2), 4 * db + 2 * dg + ((n & 3) >> 1)) +
                  8 * (n & 1);
   }
+  static_assert(TBYTES + (KVT - 8) * ROWB < 65536, "operand offsets must fit the 16-bit offset field");
 
   // ---- the phases of a tile, per wave.  The MFMA phases are written software-pipelined ("read
   // operand i+PFD, MFMA i") and pinned to that issue order with sched_group_barrier, so that LDS
@@ -426,17 +465,18 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   constexpr int NPV = KB * 2 * G::kDBlocks, NQK = KB * G::kDSteps;
   // Operand i of the fused sequence "PV of one tile, then QK^T of the next": i < NPV is a V^T
   // operand (two transposing reads: key rows 32b + 16ks + 4*half + 0..3 and the same + 8, in the
-  // row order the score accumulator dictates), the rest are K operands (one 16-byte read).
-  auto load_op = [&](int i) -> bf16x8 {
+  // row order the score accumulator dictates) from V slot VS, the rest are K operands (one
+  // 16-byte read) from K slot KS.
+  auto load_op = [&](int i, int KS, int VS) __attribute__((always_inline)) -> bf16x8 {
     if (i < NPV) {
       int db = i % G::kDBlocks, ks = (i / G::kDBlocks) & 1, b = i / (2 * G::kDBlocks);
-      return lds_read_vt(smem + vcur[db] + (32 * b + 16 * ks) * ROWB, ROWB);
+      return lds_read_vt((const lds_char *)(size_t)(vadr[db] + (unsigned)(VS * TBYTES + (32 * b + 16 * ks) * ROWB)), ROWB);
     }
     int j = i - NPV;
     int s = j % G::kDSteps, b = j / G::kDSteps;
-    return *(const lds_bf16x8 *)(smem + kcur[s] + 32 * b * ROWB);
+    return *(const lds_bf16x8 *)(size_t)(kadr[s] + (unsigned)(KS * TBYTES + 32 * b * ROWB));
   };
-  auto do_mfma = [&](int i, bf16x8 op) {
+  auto do_mfma = [&](int i, bf16x8 op) __attribute__((always_inline)) {
     if (i < NPV) {
       int db = i % G::kDBlocks, ks = (i / G::kDBlocks) & 1, b = i / (2 * G::kDBlocks);
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op, pop[b][ks], o[db], 0, 0, 0);
@@ -450,16 +490,17 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op, qreg[s], sacc[b], 0, 0, 0);
     }
   };
-  auto mfma_seq = [&](auto I0c, auto I1c, auto stagec) {
+  auto mfma_seq = [&](auto I0c, auto I1c, auto stagec, auto ksc, auto vsc) __attribute__((always_inline)) {
     constexpr int I0 = decltype(I0c)::value, I1 = decltype(I1c)::value, N = I1 - I0;
+    constexpr int KS = decltype(ksc)::value, VS = decltype(vsc)::value;  // K and V slots read
     constexpr bool STAGE = decltype(stagec)::value;  // emit this period's tile loads along the way
     constexpr int GAP = N >= NLD ? N / NLD : 1, PER = N >= NLD ? 1 : NLD / N;  // loads per MFMA slot
     bf16x8 ops[N];
 #pragma unroll
-    for (int i = 0; i < PFD && i < N; ++i) ops[i] = load_op(I0 + i);
+    for (int i = 0; i < PFD && i < N; ++i) ops[i] = load_op(I0 + i, KS, VS);
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      if (i + PFD < N) ops[i + PFD] = load_op(I0 + i + PFD);
+      if (i + PFD < N) ops[i + PFD] = load_op(I0 + i + PFD, KS, VS);
       do_mfma(I0 + i, ops[i]);
       if (STAGE && i % GAP == 0 && i / GAP * PER < NLD) {
 #pragma unroll
@@ -469,27 +510,31 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     sgb_prologue<0, N, I0, NPV, PFD>();
     sgb_steady<0, N, I0, NPV, PFD>();
   };
-  auto next_k_slot = [&]() {
-#pragma unroll
-    for (int s = 0; s < G::kDSteps; ++s) kcur[s] ^= TBYTES;
+  using slot0 = integral_constant<int, 0>;
+  using slot1 = integral_constant<int, 1>;
+  auto qk0 = [&]() __attribute__((always_inline)) {  // QK^T of a stream's first tile (K slot 0); its loads went out in the prologue
+    mfma_seq(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, false_type{}, slot0{}, slot0{});
   };
-  auto next_v_slot = [&]() {
-#pragma unroll
-    for (int db = 0; db < G::kDBlocks; ++db) vcur[db] ^= TBYTES;
+  auto pv = [&](auto vsc) __attribute__((always_inline)) {  // PV of the tile in V slot vsc
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV>{}, false_type{}, slot0{}, vsc);
   };
-  auto qk = [&](auto stagec) {  // QK^T of the tile in the current K slot
-    mfma_seq(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, stagec);
-    next_k_slot();
+  auto pv_qk = [&](auto stagec, auto parc) __attribute__((always_inline)) {  // period i of parity parc: PV of tile i-1 (V slot 1 - par), QK^T of tile i (K slot par)
+    constexpr int PAR = decltype(parc)::value;
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, stagec, parc, integral_constant<int, 1 - PAR>{});
   };
-  auto pv = [&]() {  // PV of the tile in the current V slot (slot kept)
-    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV>{}, false_type{});
-  };
-  auto pv_qk = [&](auto stagec) {  // PV of the previous tile, then QK^T of the current one
-    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, stagec);
-    next_k_slot();
-    next_v_slot();
-  };
-  auto softmax = [&](int t) {
+  // Softmax of tile t.  The common case (FIRST = false, and the tile's scores stay within 2^8 of
+  // the running max) is one pass of 3.5 VALU instructions per score: weight = exp2(score * c -
+  // max * c), added to the row sum (two independent chains), rounded to bf16 in pairs.  No tile
+  // max is computed: if a score had exceeded the running max by more than the threshold, its
+  // weight and hence the lane's tile sum would exceed 2^8, and the wave falls back to the full
+  // pass (tile max, lazy rescale of O and l, weights again from the raw scores, which the fast
+  // pass leaves untouched).  The first tile always takes the full pass (the running max starts at
+  // -inf), which also leaves the fp32 weights in sacc for the residual pass of short rows.
+  // (Summing the rounded pairs with the bf16 dot-product instruction instead would be half the
+  // additions, but measured it costs a third more cycles for the whole kernel: next to MFMAs that
+  // instruction is far from full rate.)
+  auto softmax = [&](int t, auto firstc, bool keep_fp32) __attribute__((always_inline)) {
+    constexpr bool FIRST = decltype(firstc)::value;  // keep_fp32 (wave-uniform): take the full pass, the residual pass follows
     const int base = gtile(t) * KVT;
     if (base + KVT > wlim_min) {
 #pragma unroll
@@ -500,47 +545,81 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
           if (kv >= lim) sacc[b][r] = -INFINITY;
         }
     }
-    float mx = sacc[0][0];
-#pragma unroll
-    for (int b = 0; b < KB; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[b][r]);
-    mx = fmaxf(mx, other_half(mx));
-    if (__builtin_amdgcn_ballot_w64(mx > m_used + a.tau) != 0) {  // wave-uniform, rare after tile 0
-      const float m_new = fmaxf(m_used, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * a.sl2e);
-      m_used = m_new;
-      l *= alpha;
-#pragma unroll
-      for (int db = 0; db < G::kDBlocks; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-    }
-    const float msc = m_used * a.sl2e;
     float lsum = 0.f;
+    bool full = FIRST || keep_fp32;
+    if (!full) {
+      const float msc = m_used * a.sl2e;
+      float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
-    for (int b = 0; b < KB; ++b) {
+      for (int b = 0; b < KB; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][r], a.sl2e, -msc));
-        sacc[b][r] = p;
-        lsum += p;
+        for (int ks = 0; ks < 2; ++ks) {
+          union {
+            bf16x2 h[4];
+            bf16x8 v;
+          } u;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i], a.sl2e, -msc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i + 1], a.sl2e, -msc));
+            u.h[i] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+            ls0 += p0;
+            ls1 += p1;
+          }
+          pop[b][ks] = u.v;
+        }
+      lsum = ls0 + ls1;
+      // NaN (a masked score against a running max that is still -inf) must take the full pass too
+      full = __builtin_amdgcn_ballot_w64(!(lsum <= 256.0f)) != 0;  // wave-uniform, rare
+    }
+    if (full) {
+      float mx = sacc[0][0];
+#pragma unroll
+      for (int b = 0; b < KB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[b][r]);
+      mx = fmaxf(mx, other_half(mx));
+      if (__builtin_amdgcn_ballot_w64(mx > m_used + a.tau) != 0) {  // wave-uniform
+        const float m_new = fmaxf(m_used, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * a.sl2e);
+        m_used = m_new;
+        l *= alpha;
+#pragma unroll
+        for (int db = 0; db < G::kDBlocks; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
       }
-      pop[b][0] = pack8(sacc[b], 0);
-      pop[b][1] = pack8(sacc[b], 8);
+      const float msc = m_used * a.sl2e;
+      lsum = 0.f;
+#pragma unroll
+      for (int b = 0; b < KB; ++b) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          sacc[b][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][r], a.sl2e, -msc));
+          lsum += sacc[b][r];
+        }
+        pop[b][0] = pack8(sacc[b], 0);
+        pop[b][1] = pack8(sacc[b], 8);
+      }
     }
     l += lsum;
   };
-  // Columns whose keys all lie in tile 0 (rows with at most KVT keys) take their weights as
-  // hi + lo: a second PV pass over tile 0 with the bf16 residuals of P.  Must run after
-  // softmax(0) (sacc still holds the fp32 weights) and once V(0) is visible in LDS.
-  const bool precise0 = ctx + tok0 < KVT && gtile(0) == 0;  // group-uniform
-  auto pv_residual0 = [&]() {
+  // Rows with at most kPreciseKeys keys take their weights as hi + lo: a second PV pass over the
+  // tile with the bf16 residuals of P, so that the rounding of the weights (which only averages
+  // out over many keys) stays out of the output tolerance there.  That concerns the first
+  // kPreciseKeys / KVT key tiles of the workgroups whose first query sits below position
+  // kPreciseKeys.  The pass needs the fp32 weights (the softmax's full pass leaves them in sacc)
+  // and V of that tile in LDS: it runs at the start of the following period, before QK^T
+  // overwrites sacc.
+  constexpr int kPreciseKeys = 256;
+  const bool precise_wg = ctx + tok0 < kPreciseKeys;  // group-uniform
+  auto precise = [&](int i) __attribute__((always_inline)) { return precise_wg && i >= 0 && gtile(i) * KVT < kPreciseKeys; };
+  auto pv_residual = [&](auto vsc) __attribute__((always_inline)) {
 #pragma unroll
     for (int b = 0; b < KB; ++b)
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) pop[b][ks] = pack8_residual(sacc[b], 8 * ks, pop[b][ks]);
-    pv();
+    pv(vsc);
 #pragma unroll
     for (int b = 0; b < KB; ++b)  // back to the rounded weights (cheaper than keeping a copy live)
 #pragma unroll
@@ -556,14 +635,15 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     for (int g = 0; g < NSTREAM; ++g) {
       const int gt0 = stream_tile(g, 0), gt1 = stream_tile(g, 1);
       const int pg0 = page_of(gt0), pg1 = page_of(gt1);
-      TileLoad k0 = dma_prep(false, g, gt0, pg0, 0), v0 = dma_prep(true, g, gt0, pg0, 0);
+      TileLoad k0 = dma_prep(false, g, gt0, pg0, 0);
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) dma_emit(k0, voff[g][0][j], j);
+      TileLoad v0 = dma_prep(true, g, gt0, pg0, 0);
+#pragma unroll
+      for (int j = 0; j < NIW; ++j) dma_emit(v0, voff[g][1][j], j);
       TileLoad k1 = dma_prep(false, g, gt1, pg1, 1);
 #pragma unroll
-      for (int j = 0; j < NIW; ++j) dma_emit(false, k0, j);
-#pragma unroll
-      for (int j = 0; j < NIW; ++j) dma_emit(true, v0, j);
-#pragma unroll
-      for (int j = 0; j < NIW; ++j) dma_emit(false, k1, j);
+      for (int j = 0; j < NIW; ++j) dma_emit(k1, voff[g][0][j], j);
       pg_k[g] = page_of(stream_tile(g, 2));
       pg_v[g] = pg1;
     }
@@ -576,52 +656,74 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // exponentiates tile t; the second group first exponentiates tile t-1 and then multiplies.
   // One wave of each group sits on every SIMD, so the matrix pipe and the VALU are both busy
   // through the whole period, and since nothing forces the phase boundary to line up, a short
-  // softmax simply lets the next MFMA phase start early.
+  // softmax simply lets the next MFMA phase start early.  Wave priorities are left alone: raising
+  // the multiplying wave (or the other one) measured 5 % more cycles for the whole kernel.
   // Buffer hand-off: from period 1 on, K(t+1) and V(t) are requested in the first group's MFMA
   // phase of period t into the slots last read in period t-1, have landed before the barrier
-  // that ends period t, and are first read in period t+1.
-  if (grp == 0) {  // always has Tl == P >= 1
-    __builtin_amdgcn_s_setprio(3);
-    qk(false_type{});  // the loads of period 0 went out in the prologue
-    __builtin_amdgcn_s_setprio(0);
-    softmax(0);
-    __syncthreads();
-    if (precise0) pv_residual0();  // V(0) became visible at the barrier; sacc still holds P(0)
-    for (int t = 1; t < Tl; ++t) {
-      issue_prep(t);
-      __builtin_amdgcn_s_setprio(3);
-      pv_qk(true_type{});
-      __builtin_amdgcn_s_setprio(0);
-      softmax(t);
-      wait_loads();
+  // that ends period t, and are first read in period t+1.  Periods alternate between two copies
+  // of the loop body, one per slot parity.
+  // The tile loop exists twice: the few workgroups that hold rows of at most kPreciseKeys keys
+  // (at most eight key tiles long) take the copy with the residual passes, everything else the
+  // copy without them, whose registers and schedule the rare case then cannot disturb.
+  auto tile_loop = [&](auto precc) __attribute__((always_inline)) {
+    constexpr bool PREC = decltype(precc)::value;
+    if (grp == 0) {  // always has Tl == P >= 1
+      qk0();  // the loads of period 0 went out in the prologue
+      softmax(0, true_type{}, false);
       __syncthreads();
-    }
-    __builtin_amdgcn_s_setprio(3);
-    pv();
-    __builtin_amdgcn_s_setprio(0);
-  } else {  // SPLIT: may have one tile less than the first group, or none
-    if (Tl > 0) {
-      __builtin_amdgcn_s_setprio(3);
-      qk(false_type{});
-      __builtin_amdgcn_s_setprio(0);
-    }
-    __syncthreads();
-    if (Tl > 0) {
-      softmax(0);
-      if (precise0) pv_residual0();
-      for (int t = 1; t < Tl; ++t) {
-        __builtin_amdgcn_s_setprio(3);
-        pv_qk(false_type{});
-        __builtin_amdgcn_s_setprio(0);
+      auto period = [&](int t, auto parc) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(parc)::value;
+        if (PREC && precise(t - 1)) pv_residual(integral_constant<int, 1 - PAR>{});  // V(t-1) became visible at the barrier
+        issue_prep(t, parc);
+        pv_qk(true_type{}, parc);
+        softmax(t, false_type{}, PREC && precise(t));
+        wait_loads();
         __syncthreads();
-        softmax(t);
+      };
+      int t = 1;
+      for (; t + 1 < Tl; t += 2) {  // single-exit loop over pairs of periods; an odd one out follows it
+        period(t, slot1{});
+        period(t + 1, slot0{});
       }
-      __builtin_amdgcn_s_setprio(3);
-      pv();
-      __builtin_amdgcn_s_setprio(0);
+      if (t < Tl) {
+        period(t, slot1{});
+        if (PREC && precise(t)) pv_residual(slot1{});
+        pv(slot1{});
+      } else {
+        if (PREC && precise(t - 1)) pv_residual(slot0{});
+        pv(slot0{});
+      }
+    } else {  // SPLIT: may have one tile less than the first group, or none
+      if (Tl > 0) qk0();
+      __syncthreads();
+      if (Tl > 0) {
+        softmax(0, true_type{}, false);
+        auto period = [&](int t, auto parc) __attribute__((always_inline)) {
+          constexpr int PAR = decltype(parc)::value;
+          if (PREC && precise(t - 1)) pv_residual(integral_constant<int, 1 - PAR>{});
+          pv_qk(false_type{}, parc);
+          __syncthreads();
+          softmax(t, false_type{}, PREC && precise(t));
+        };
+        int t = 1;
+        for (; t + 1 < Tl; t += 2) {
+          period(t, slot1{});
+          period(t + 1, slot0{});
+        }
+        if (t < Tl) {
+          period(t, slot1{});
+          if (PREC && precise(t)) pv_residual(slot1{});
+          pv(slot1{});
+        } else {
+          if (PREC && precise(t - 1)) pv_residual(slot0{});
+          pv(slot0{});
+        }
+      }
+      for (int t = max(Tl, 1); t < P; ++t) __syncthreads();  // keep the barrier count of the first group
     }
-    for (int t = max(Tl, 1); t < P; ++t) __syncthreads();  // keep the barrier count of the first group
-  }
+  };
+  if (precise_wg) tile_loop(true_type{});
+  else tile_loop(false_type{});
 
   if (SPLIT) {
     // ---- merge the second group's running state into the first group's (same columns, same
