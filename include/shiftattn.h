@@ -151,6 +151,26 @@ int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out,
                    float scale, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * sp_attn_decode_static — sp_attn_decode for callers that cannot allocate or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments and same result, bit for bit, as sp_attn_decode, but the per-split
+ * partials live in a static device array inside the library (16 MiB, held on every GPU the
+ * library has run this call on until the process ends), and the call makes no allocation of
+ * any kind.
+ *   - Shapes whose partials exceed 16 MiB (sp_attn_decode_workspace_size(...) > 16 MiB) are
+ *     refused with SP_ERR_WORKSPACE before anything is launched.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one GPU (two
+ *     streams, two threads) race and must be serialised by the caller.  The array needs no
+ *     clearing between calls (every slot is written by the launch that reads it).
+ *   - The first call on a device looks up the array's device address (and sets kernel
+ *     attributes); make that call outside any stream capture.
+ */
+int sp_attn_decode_static(const sp_cache_desc *cache, const void *q, void *out,
+                          const int32_t *seq_lens, const int32_t *block_table, int32_t batch,
+                          int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads,
+                          float scale, void *stream);
+
+/*
  * sp_chunk_step — one chunk step in one call: sp_kv_append of every sequence's new tokens
  * followed by sp_attn_prefill over them (chunked prefill, or the verification step of
  * speculative decoding: the last accepted token plus the draft tokens).

@@ -27,7 +27,7 @@ SP_ERR_WORKSPACE = -4
 SP_ERR_HIP = -5
 
 EXPORTS = (
-    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_decode_step", "sp_chunk_step", "sp_ulysses_pack", "sp_ulysses_unpack",
+    "sp_kv_append", "sp_attn_prefill", "sp_attn_decode", "sp_attn_decode_static", "sp_decode_step", "sp_chunk_step", "sp_ulysses_pack", "sp_ulysses_unpack",
     "sp_attn_prefill_workspace_size",
     "sp_attn_decode_workspace_size", "sp_debug_validate_metadata", "sp_debug_validate_hints", "sp_debug_set_tuning",
     "sp_status_string", "sp_last_error", "sp_version",
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.sp_attn_prefill.restype = ctypes.c_int
         L.sp_attn_decode.argtypes = [cd, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, sz, vp]
         L.sp_attn_decode.restype = ctypes.c_int
+        L.sp_attn_decode_static.argtypes = [cd, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp]
+        L.sp_attn_decode_static.restype = ctypes.c_int
         L.sp_decode_step.argtypes = [cd, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, sz, vp]
         L.sp_decode_step.restype = ctypes.c_int
         L.sp_chunk_step.argtypes = [cd, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
@@ -197,6 +199,14 @@ def sp_attn_decode(cache: KVCache, q, out, seq_lens, block_table, max_seq_len: i
     _check(lib().sp_attn_decode(ctypes.byref(cache.desc), _ptr(q), _ptr(out), _ptr(seq_lens),
                                 _ptr(block_table), batch, max_pages, max_seq_len, num_q_heads, float(scale),
                                 _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def sp_attn_decode_static(cache: KVCache, q, out, seq_lens, block_table, max_seq_len: int, scale: float, stream=None) -> None:
+    """sp_attn_decode with the partials in the library's static device array (no workspace, no
+    allocation); shapes whose partials exceed 16 MiB are refused."""
+    batch, max_pages = block_table.shape
+    _check(lib().sp_attn_decode_static(ctypes.byref(cache.desc), _ptr(q), _ptr(out), _ptr(seq_lens), _ptr(block_table),
+                                       batch, max_pages, max_seq_len, q.shape[1], float(scale), _stream(stream)))
 
 
 def sp_decode_step(cache: KVCache, k_new, v_new, q, out, seq_lens, block_table, max_seq_len: int, scale: float,

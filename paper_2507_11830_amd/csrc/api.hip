@@ -136,6 +136,22 @@ int sp_attn_decode(const sp_cache_desc *cache, const void *q, void *out, const i
                        max_pages_per_seq, max_seq_len, num_q_heads, scale, workspace, workspace_bytes, stream);
 }
 
+int sp_attn_decode_static(const sp_cache_desc *cache, const void *q, void *out, const int32_t *seq_lens,
+                          const int32_t *block_table, int32_t batch, int32_t max_pages_per_seq, int32_t max_seq_len,
+                          int32_t num_q_heads, float scale, void *stream) {
+  if (int rc = check_cache(cache)) return rc;
+  if (int rc = check_heads(cache, num_q_heads)) return rc;
+  if (int rc = check_scale(scale)) return rc;
+  if (batch < 0 || max_pages_per_seq < 0 || max_seq_len < 0)
+    return fail(SP_ERR_BAD_SHAPE, "negative count in sp_attn_decode_static");
+  if (batch == 0) return SP_OK;
+  if (!q || !out || !seq_lens || !block_table) return fail(SP_ERR_NULL, "sp_attn_decode_static: NULL argument");
+  if (max_pages_per_seq == 0 && max_seq_len > 0)
+    return fail(SP_ERR_BAD_SHAPE, "max_pages_per_seq=0 with max_seq_len=%d", max_seq_len);
+  return launch_decode_static(*cache, q, out, seq_lens, block_table, batch, max_pages_per_seq, max_seq_len,
+                              num_q_heads, scale, (hipStream_t)stream);
+}
+
 int sp_decode_step(const sp_cache_desc *cache, const void *k_new, const void *v_new, const void *q, void *out,
                    const int32_t *seq_lens, const int32_t *block_table, int32_t batch,
                    int32_t max_pages_per_seq, int32_t max_seq_len, int32_t num_q_heads, float scale,

@@ -17,6 +17,8 @@
 // summation order, one round-to-nearest-even to bf16.
 //
 // Bound: HBM bandwidth.  Algorithmic bytes: 4 * head_dim per cached token per KV head.
+#include <mutex>
+
 #include "attn_tile.h"
 
 namespace sp {
@@ -820,6 +822,49 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
   a.part_ml = a.part_o + (size_t)batch * num_q_heads * a.nsplit * c.head_dim;
   if (c.head_dim == 128) return launch_decode_d<128>(a, (char *)out, batch, stream);
   return launch_decode_d<64>(a, (char *)out, batch, stream);
+}
+
+// ---- sp_attn_decode_static: the same decode for callers that cannot hand over a workspace
+// (nor let anyone allocate one): the per-split partials go to a file-scope device array.  The
+// array's name is only a host-side handle; its device address is asked for once per device, with
+// that device current, and kept.  Nothing in it has to start at zero (every partial slot is
+// written by the launch that reads it), so no clearing is needed between calls.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, 0 = not asked yet
+static std::mutex g_scratch_mu;
+
+static int static_scratch(void **ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(SP_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(SP_ERR_UNSUPPORTED, "device ordinal %d (at most %d devices)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return fail(SP_ERR_HIP, "hipGetSymbolAddress(scratch): %s", e != hipSuccess ? hipGetErrorString(e) : "null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return SP_OK;
+}
+
+size_t decode_static_scratch_bytes() { return kStaticScratchBytes; }
+
+int launch_decode_static(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
+                         const int32_t *block_table, int batch, int max_pages, int max_seq_len, int num_q_heads,
+                         float scale, hipStream_t stream) {
+  const size_t need = decode_workspace_bytes(batch, max_seq_len, num_q_heads, c.head_dim);
+  if (need > kStaticScratchBytes)
+    return fail(SP_ERR_WORKSPACE, "sp_attn_decode_static: this shape needs %zu bytes of partials, the static scratch holds %zu",
+                need, kStaticScratchBytes);
+  void *ws = nullptr;
+  if (int rc = static_scratch(&ws)) return rc;
+  return launch_decode(c, nullptr, nullptr, q, out, seq_lens, block_table, batch, max_pages, max_seq_len, num_q_heads,
+                       scale, ws, kStaticScratchBytes, stream);
 }
 
 }  // namespace sp

@@ -68,6 +68,12 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
                   int max_seq_len, int num_q_heads, float scale, void *workspace, size_t workspace_bytes,
                   hipStream_t stream);
 
+// sp_attn_decode_static: partials in the library's own static device array instead of a workspace.
+size_t decode_static_scratch_bytes();
+int launch_decode_static(const sp_cache_desc &c, const void *q, void *out, const int32_t *seq_lens,
+                         const int32_t *block_table, int batch, int max_pages, int max_seq_len, int num_q_heads,
+                         float scale, hipStream_t stream);
+
 // Short query chunks (a few tokens per sequence on long prefixes) on the decode split kernel:
 // same arguments as launch_prefill.  Returns 1 without launching anything when the shape or the
 // workspace does not qualify; decode_multi_workspace_bytes is 0 for shapes that never qualify.

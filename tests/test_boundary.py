@@ -142,6 +142,13 @@ def test_argument_validation_needs_no_gpu(built_lib):
     assert L.sp_chunk_step(ctypes.byref(d), None, one, one, one, one, one, one, 4, 64, 16, 4, 1000, 8, 0.1, one, 1 << 30, None) == sp.SP_ERR_NULL
     assert L.sp_chunk_step(ctypes.byref(d), one, one, one, one, one, one, one, 4, 64, 16, 4, 1000, 0, 0.1, one, 1 << 30, None) == sp.SP_ERR_BAD_SHAPE
     assert L.sp_chunk_step(ctypes.byref(d), one, one, one, one, one, one, one, 0, 64, 0, 0, 0, 8, 0.1, None, 0, None) == sp.SP_OK
+    # the allocation-free decode: same validation, and shapes beyond its 16 MiB static array are refused
+    assert L.sp_attn_decode_static(ctypes.byref(bad_dim), one, one, one, one, 1, 1, 16, 8, ctypes.c_float(0.1), None) == sp.SP_ERR_UNSUPPORTED
+    assert L.sp_attn_decode_static(ctypes.byref(d), one, None, one, one, 1, 1, 16, 8, ctypes.c_float(0.1), None) == sp.SP_ERR_NULL
+    assert L.sp_attn_decode_static(ctypes.byref(d), one, one, one, one, 0, 1, 16, 8, ctypes.c_float(0.1), None) == sp.SP_OK
+    assert sp.sp_attn_decode_workspace_size(4096, 16384, 32, 128) > 16 << 20
+    assert L.sp_attn_decode_static(ctypes.byref(d), one, one, one, one, 4096, 1024, 16384, 32, ctypes.c_float(0.1), None) == sp.SP_ERR_WORKSPACE
+    assert b"static scratch" in L.sp_last_error()
     # empty batches are legal no-ops
     assert L.sp_attn_prefill(ctypes.byref(d), one, one, one, one, one, 0, 1, 0, 0, 0, 8, 0.1, 1, None, 0, None) == sp.SP_OK
     assert L.sp_attn_decode(ctypes.byref(d), one, one, one, one, 0, 1, 0, 8, 0.1, None, 0, None) == sp.SP_OK
