@@ -693,6 +693,12 @@ def main():
         "decode_warm": {"ms": warm, "GBps": dec.bytes / warm["mean"] / 1e6,
                         "note": "C3 on a single pool copy: served by the last-level cache, not HBM"},
     }
+    # the same decode with the combine pass folded into the split kernel (last-arriving wave merges;
+    # off by default: the device-scope release every wave then needs costs far more than a launch)
+    sp.sp_debug_set_tuning("decode_fuse", 2)
+    fus = time_one(lambda: dec.attend(dec.next_cache()), args.steps, args.warmup)
+    sp.sp_debug_set_tuning("decode_fuse", 0)
+    res["decode_combine_in_split_kernel"] = {"ms": fus, "GBps": dec.bytes / fus["mean"] / 1e6}
     fz = time_one(lambda: dec.fused_step(dec.next_cache()), args.steps, args.warmup)
     # the same step captured once per KV-pool copy in a HIP graph and replayed (the library only
     # enqueues, so it is capture-safe; a graph takes the host out of the launch path)

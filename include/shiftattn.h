@@ -274,6 +274,10 @@ int sp_debug_validate_hints(const int32_t *cu_seqlens, const int32_t *lens, int3
  *   "decode_ring"   32-key blocks a decode wave keeps in its LDS ring (one computed on, the
  *                   rest in flight): 0 (built-in choice), 2..4, or 1 for two K blocks and a
  *                   single V block (less LDS per wave, one more resident wave per CU).
+ *   "decode_fuse"   where the log-sum-exp combine of sp_attn_decode / sp_decode_step runs: 0 (built-in
+ *                   choice: a kernel of its own), 1 (the same), 2 (inside the split kernel, by the
+ *                   wave of a (sequence, head group) that finishes last; only taken up to 32
+ *                   splits; slower on this chip, kept for measurement).
  *   "combine_form"  work of a wave of the log-sum-exp combine kernel: 0 (built-in choice on the row
  *                   count), 1 (one 32-channel slice of a row), 2 (a whole row; only taken up to
  *                   64 splits per row).

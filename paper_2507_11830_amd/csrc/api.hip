@@ -270,6 +270,11 @@ int sp_debug_set_tuning(const char *key, int32_t value) {
     set_decode_ring(value);
     return SP_OK;
   }
+  if (!strcmp(key, "decode_fuse")) {
+    if (value < 0 || value > 2) return fail(SP_ERR_UNSUPPORTED, "decode_fuse=%d (0, 1 or 2)", value);
+    set_decode_fuse(value);
+    return SP_OK;
+  }
   if (!strcmp(key, "prefill_kv_splits")) {
     if (value < 0 || value > 16) return fail(SP_ERR_UNSUPPORTED, "prefill_kv_splits=%d (0..16)", value);
     set_prefill_kv_splits(value);

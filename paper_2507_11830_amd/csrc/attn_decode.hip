@@ -17,6 +17,7 @@
 // summation order, one round-to-nearest-even to bf16.
 //
 // Bound: HBM bandwidth.  Algorithmic bytes: 4 * head_dim per cached token per KV head.
+#include <atomic>
 #include <mutex>
 
 #include "attn_tile.h"
@@ -35,6 +36,8 @@ struct DecodeArgs {
   float *part_ml;  // [row][nsplit][2]  (m in log2 units, l)
   int max_pages, num_pages, Hq, Hkv, group, geff, n_hgroups, chunk, nsplit;
   int q_cap;  // MQ kernels: query tokens per tile (32 / geff)
+  int32_t *arrive;  // FUSE kernels: one arrival counter per (sequence, head group), zero between launches
+  char *out;        // FUSE kernels: bf16 [batch][Hq][D]
   float sl2e;
   float tau;  // lazy-rescale threshold in raw score units (8 / sl2e)
 };
@@ -99,6 +102,100 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Fused combine (FUSE forms of the split kernel; OFF by default, tuning key "decode_fuse").  Every
+// wave of a (sequence, head group) — the ones without keys too — announces itself on that pair's
+// arrival counter after its partial is visible device-wide; the wave that arrives last merges
+// the pair's partials and writes the output rows, so the decode step is ONE launch.
+// Measured, it loses badly on this chip: the partials of one sequence are written on all eight
+// XCDs, whose L2 caches are not coherent with each other, so every wave needs a device-scope
+// release (an L2 write-back) in front of its arrival, and with hundreds of waves executing one
+// each the 64-sequence decode batch takes 106 us against 33 us for split + combine as two
+// launches — the kernel boundary is the cheap device-wide release here.  Plain write-through
+// stores plus a wait instead of the fence are not enough (seen: a merging wave reading a slot
+// before the other XCD's store had landed).  The counters live in a device array of the
+// library, start at zero and are reset by the merging wave, i.e. they are zero again when the
+// kernel ends; nothing has to be cleared between launches.
+//
+// The merge itself: eight lanes per head (eight heads per pass), lane j of a head holds the
+// (m, l) pairs of the splits j, j + 8, ... (at most four: the form is used up to 32 splits) and
+// 16 channels of the output row.  Weights are exchanged inside the eight-lane groups; the partial
+// rows are requested eight splits at a time, all of them before the first is used.  Summation
+// order is fixed (split index ascending), so the result does not depend on which wave merges.
+template <int D>
+__device__ __forceinline__ void arrive_and_merge(const DecodeArgs &a, int lane, int seq, int head0, int ncols) {
+  static_assert(D == 128 || D == 64, "head_dim");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // this wave's partial is visible to the whole device before its arrival is
+  int old = 0;
+  if (lane == 0) old = __hip_atomic_fetch_add(a.arrive + blockIdx.y, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  old = __builtin_amdgcn_readfirstlane(old);
+  if (old != (int)gridDim.x - 1) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // every other wave's partial is visible to this one
+  if (lane == 0) a.arrive[blockIdx.y] = 0;  // clean for the next launch
+  const int nsplit = a.nsplit;  // <= 32
+  constexpr int CPL = D / 8;    // channels per lane
+  const int j = lane & 7;
+  for (int h0 = 0; h0 < ncols; h0 += 8) {  // uniform
+    const int hh = h0 + (lane >> 3);
+    const bool hv = hh < ncols;
+    const long row = (long)seq * a.Hq + head0 + (hv ? hh : 0);
+    const f32x2 *ml = reinterpret_cast<const f32x2 *>(a.part_ml) + row * nsplit;
+    const float *po = a.part_o + row * nsplit * D + j * CPL;
+    f32x2 w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) w[u] = ml[min(8 * u + j, nsplit - 1)];
+    // the first eight partial rows go out with the (m, l) pairs: one round trip for small split counts
+    f32x4 v[8][CPL / 4];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+      for (int c = 0; c < CPL / 4; ++c) v[k][c] = *reinterpret_cast<const f32x4 *>(po + (long)min(k, nsplit - 1) * D + 4 * c);
+    float M = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) M = fmaxf(M, 8 * u + j < nsplit ? w[u][0] : -INFINITY);
+#pragma unroll
+    for (int o = 1; o <= 4; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
+    float f[4], den = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool live = 8 * u + j < nsplit && w[u][0] != -INFINITY;
+      f[u] = live ? __builtin_amdgcn_exp2f(w[u][0] - M) : 0.f;
+      den += live ? f[u] * w[u][1] : 0.f;
+    }
+#pragma unroll
+    for (int o = 1; o <= 4; o <<= 1) den += __shfl_xor(den, o);
+    f32x4 acc[CPL / 4];
+#pragma unroll
+    for (int c = 0; c < CPL / 4; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (8 * u >= nsplit) break;  // uniform
+      if (u > 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+          for (int c = 0; c < CPL / 4; ++c)
+            v[k][c] = *reinterpret_cast<const f32x4 *>(po + (long)min(8 * u + k, nsplit - 1) * D + 4 * c);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float fk = __shfl(f[u], (lane & ~7) | k);  // weight of split 8u + k (0 past the end or empty)
+#pragma unroll
+        for (int c = 0; c < CPL / 4; ++c)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[c][e] += fk != 0.f ? fk * v[k][c][e] : 0.f;
+      }
+    }
+    if (hv) {
+      const float inv = M == -INFINITY ? 0.f : 1.0f / den;  // a row without keys: zeros
+      char *dst = a.out + (row * D + j * CPL) * 2;
+#pragma unroll
+      for (int c = 0; c < CPL / 4; ++c)
+        *reinterpret_cast<bf16x4 *>(dst + 8 * c) =
+            __builtin_convertvector(M == -INFINITY ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[c] * inv, bf16x4);
+    }
+  }
+}
+
 // APPEND = true is the fused decode step: seq_lens counts a new token whose K/V row is NOT in the
 // cache yet but in k_new / v_new.  The wave whose range holds that position writes the row into
 // its page (for later steps) and patches it into its own LDS copy of the last block (for this
@@ -117,9 +214,12 @@ __device__ __forceinline__ void wait_vmcnt() {
 // same single read of K and V: every K / V operand taken from LDS feeds one multiply per tile.
 // The second set of accumulators costs nothing in residency: LDS already limits a CU to four of
 // these waves, one per SIMD, so each may use the whole register file.
-template <int D, int NB, bool APPEND, bool MQ, int NT = 1>
+//
+// FUSE = true (single-token forms only) folds the combine pass into this kernel: see arrive_and_merge.
+template <int D, int NB, bool APPEND, bool MQ, int NT = 1, bool FUSE = false>
 __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(DecodeArgs a) {
   static_assert(NT == 1 || MQ, "several column tiles only make sense with several query tokens");
+  static_assert(!FUSE || !MQ, "the fused combine serves the single-token forms");
   using G = TileGeom<D>;
   using Z = SwzTile<D>;
   constexpr int ROWB = D * 2;           // bytes of one K or V row
@@ -214,6 +314,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
     for (int nt = 0; nt < NT; ++nt)
       if (lane < 32 && col_valid[nt])
         *reinterpret_cast<f32x2 *>(a.part_ml + (row_col[nt] * a.nsplit + split) * 2) = (f32x2){-INFINITY, 0.f};
+    if (FUSE) arrive_and_merge<D>(a, lane, seq, head0, ncols);
     return;
   }
   const int kv1 = min(kv_end, kv0 + a.chunk);
@@ -516,6 +617,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
         *reinterpret_cast<f32x2 *>(a.part_ml + pidx * 2) = (f32x2){MQ && lt == 0.f ? -INFINITY : m[nt] * a.sl2e, lt};
     }
   }
+  if (FUSE) arrive_and_merge<D>(a, lane, seq, head0, ncols);
 }
 
 // Broadcast of lane k's float (k wave-uniform); the builtin is integer-typed, so bit-cast.
@@ -676,11 +778,11 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
   return SP_OK;
 }
 
-template <int D, int NB, bool APPEND, bool MQ = false, int NT = 1>
+template <int D, int NB, bool APPEND, bool MQ = false, int NT = 1, bool FUSE = false>
 static int launch_split(const DecodeArgs &a, int batch, hipStream_t stream) {
   static bool attr_set = false;  // benign if two threads race
   constexpr int smem = (NB == 1 ? 3 : 2 * NB) * 32 * D * 2;  // NB = 1: two K blocks and one V block
-  auto fn = decode_split_kernel<D, NB, APPEND, MQ, NT>;
+  auto fn = decode_split_kernel<D, NB, APPEND, MQ, NT, FUSE>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return fail(SP_ERR_HIP, "decode smem attribute: %s", hipGetErrorString(e));
@@ -690,12 +792,59 @@ static int launch_split(const DecodeArgs &a, int batch, hipStream_t stream) {
   return SP_OK;
 }
 
+// Arrival counters of the fused combine: a device array of the library (zero at load, left zero by
+// every launch).  Each launch takes its own run of counters from a ring, so launches that overlap
+// (other streams, other threads) do not share any; a launch recorded in a HIP graph keeps the run it
+// was captured with.  As with every file-scope device variable, the array's name is only a
+// host-side handle: its device address is looked up once per device.
+constexpr int kArriveSlots = 1 << 18;
+constexpr int kArriveRing = kArriveSlots - 65536;  // a launch needs at most 65535 counters
+static __device__ int32_t g_arrive[kArriveSlots];
+constexpr int kMaxDevices = 64;
+static int32_t *g_arrive_ptr[kMaxDevices];
+static std::mutex g_symbol_mu;
+static std::atomic<unsigned> g_arrive_next{0};
+static thread_local int g_fuse_mode = 0;  // tuning hook: 0 built-in choice (separate combine kernel), 1 the same, 2 fused where possible
+void set_decode_fuse(int mode) { g_fuse_mode = mode; }
+
+static int arrive_counters(int n, int32_t **ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(SP_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(SP_ERR_UNSUPPORTED, "device ordinal %d (at most %d devices)", dev, kMaxDevices);
+  {
+    std::lock_guard<std::mutex> lock(g_symbol_mu);
+    if (!g_arrive_ptr[dev]) {
+      void *p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_arrive));
+      if (e != hipSuccess || !p)
+        return fail(SP_ERR_HIP, "hipGetSymbolAddress(arrival counters): %s", e != hipSuccess ? hipGetErrorString(e) : "null address");
+      g_arrive_ptr[dev] = (int32_t *)p;
+    }
+  }
+  *ptr = g_arrive_ptr[dev] + g_arrive_next.fetch_add((unsigned)n) % kArriveRing;
+  return SP_OK;
+}
+
 template <int D>
 static int launch_decode_d(DecodeArgs &a, char *out, int batch, hipStream_t stream) {
   long gy = (long)batch * a.n_hgroups;
   if (gy > 65535) return fail(SP_ERR_BAD_SHAPE, "sp_attn_decode: batch * head groups = %ld exceeds 65535", gy);
   const int ring = g_ring_override > 0 ? g_ring_override : 2;  // deeper rings and the 24 KiB form time the same or worse
+  // One launch instead of two (combine by the last-arriving wave, up to 32 splits): only on request,
+  // it measured three times slower than two launches (see arrive_and_merge).
+  const bool fuse = a.nsplit <= 32 && ring == 2 && g_fuse_mode == 2;
   int rc;
+  if (fuse) {
+    if (int e = arrive_counters((int)gy, &a.arrive)) return e;
+    a.out = out;
+    rc = a.k_new ? launch_split<D, 2, true, false, 1, true>(a, batch, stream)
+                 : launch_split<D, 2, false, false, 1, true>(a, batch, stream);
+    if (rc != SP_OK) return rc;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SP_ERR_HIP, "decode launch: %s", hipGetErrorString(e));
+    return SP_OK;
+  }
   if (a.k_new) rc = launch_split<D, 2, true>(a, batch, stream);  // fused step: the measured-best ring only
   else rc = ring == 1 ? launch_split<D, 1, false>(a, batch, stream)
           : ring == 2 ? launch_split<D, 2, false>(a, batch, stream)
@@ -760,6 +909,8 @@ int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v
   a.v_new = (const char *)v_new;
   a.q = (const char *)q;
   a.seq_lens = nullptr;
+  a.arrive = nullptr;
+  a.out = nullptr;
   a.cu_q = cu_q;
   a.ctx_lens = ctx_lens;
   a.block_table = block_table;
@@ -805,6 +956,8 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
   a.v_new = (const char *)v_new;
   a.q = (const char *)q;
   a.seq_lens = seq_lens;
+  a.arrive = nullptr;
+  a.out = nullptr;
   a.cu_q = a.ctx_lens = nullptr;
   a.block_table = block_table;
   a.max_pages = max_pages;
@@ -831,16 +984,14 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
 // written by the launch that reads it), so no clearing is needed between calls.
 constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
-constexpr int kMaxDevices = 64;
 static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, 0 = not asked yet
-static std::mutex g_scratch_mu;
 
 static int static_scratch(void **ptr) {
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return fail(SP_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
   if (dev < 0 || dev >= kMaxDevices) return fail(SP_ERR_UNSUPPORTED, "device ordinal %d (at most %d devices)", dev, kMaxDevices);
-  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  std::lock_guard<std::mutex> lock(g_symbol_mu);
   if (!g_scratch_ptr[dev]) {
     void *p = nullptr;
     e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));

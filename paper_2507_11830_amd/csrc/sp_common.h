@@ -48,6 +48,7 @@ int launch_ulysses(bool pack, const void *src, void *dst, int T_loc, int H, int 
 // Tuning hooks behind sp_debug_set_tuning (0 restores the built-in heuristic).
 void set_decode_chunk(int chunk);
 void set_combine_form(int form);  // combine kernel: 0 heuristic, 1 one 32-channel slice per wave, 2 a whole row per wave
+void set_decode_fuse(int mode);    // combine pass of the single-token decode: 0 heuristic, 1 separate kernel, 2 inside the split kernel (up to 32 splits)
 void set_decode_ring(int slots);   // LDS ring depth of the decode split kernel: 0 heuristic, 2..4, 1 = two K blocks + one V block
 void set_prefill_kv_splits(int n);  // pieces a query tile's key range is cut into: 0 heuristic, 1..16
 void set_prefill_short_chunk(int mode);  // 0 heuristic, 1 short query chunks stay on the prefill kernel

@@ -175,7 +175,9 @@ def test_tuning_keys_are_validated(built_lib):
         assert L.sp_debug_set_tuning(b"prefill_order", v) == want
     for v, want in [(1, sp.SP_OK), (2, sp.SP_OK), (3, sp.SP_ERR_UNSUPPORTED)]:
         assert L.sp_debug_set_tuning(b"combine_form", v) == want
-    for key in (b"decode_chunk", b"decode_ring", b"prefill_split", b"prefill_kv_splits", b"prefill_short_chunk",
+    for v, want in [(1, sp.SP_OK), (2, sp.SP_OK), (3, sp.SP_ERR_UNSUPPORTED), (-1, sp.SP_ERR_UNSUPPORTED)]:
+        assert L.sp_debug_set_tuning(b"decode_fuse", v) == want
+    for key in (b"decode_fuse", b"decode_chunk", b"decode_ring", b"prefill_split", b"prefill_kv_splits", b"prefill_short_chunk",
                 b"prefill_order", b"combine_form"):
         assert L.sp_debug_set_tuning(key, 0) == sp.SP_OK
 

@@ -341,6 +341,7 @@ def test_combine_kernel_forms(form):
     import paper_2507_11830_amd as sp
 
     sp.sp_debug_set_tuning("combine_form", form)
+    sp.sp_debug_set_tuning("decode_fuse", 1)      # keep the combine a kernel of its own
     sp.sp_debug_set_tuning("decode_chunk", 128)
     sp.sp_debug_set_tuning("prefill_kv_splits", 5)
     try:
@@ -351,8 +352,59 @@ def test_combine_kernel_forms(form):
         run_full_compare(custom_workload(f"comb-s-{form}", lens + 3, lens, 8, 1, 128, "prefill", seed=87), check_cache=False)
         run_full_compare(custom_workload(f"comb-p-{form}", lens + 40, lens, 8, 1, 128, "prefill", seed=88), check_cache=False)
     finally:
-        for key in ("combine_form", "decode_chunk", "prefill_kv_splits"):
+        for key in ("combine_form", "decode_fuse", "decode_chunk", "prefill_kv_splits"):
             sp.sp_debug_set_tuning(key, 0)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 1, 128), (32, 8, 128), (64, 1, 128), (40, 1, 64), (6, 2, 64)])
+def test_decode_combine_inside_and_outside_the_split_kernel(Hq, Hkv, d):
+    """Up to 32 splits per sequence the last-arriving wave of a (sequence, head group) merges the
+    partials inside the split kernel (one launch); the tuning key forces the separate combine
+    kernel.  Both against the oracle, on sequences with 1 .. 32 splits, empty sequences and every
+    head-tile shape (8, 4, 32 and 1 heads per wave; a group of 6 split 3 + 3), through
+    sp_attn_decode and sp_decode_step; the fused result is bitwise reproducible, and the arrival
+    counters are left clean (the second and third call reuse them)."""
+    import torch
+    import paper_2507_11830_amd as sp
+
+    lens = np.array([4096, 1, 130, 2049, 0, 777, 33, 3967, 128, 129])
+    dec = np.where(lens > 0, lens, 1)
+    sp.sp_debug_set_tuning("decode_chunk", 128)
+    try:
+        outs = {}
+        for fuse in (2, 1, 2):
+            sp.sp_debug_set_tuning("decode_fuse", fuse)
+            w = custom_workload(f"fuse-{Hq}-{Hkv}-{d}", dec, dec - 1, Hq, Hkv, d, "decode", seed=131)
+            g, o = GpuRunner(w), OracleRunner(w)
+            for st in w.steps():
+                o.append(st)
+                if st.kind == "fill":
+                    g.append(st)
+            want = o.attend(st)
+            got_step = g.decode_step(st)                    # appends inside the kernel
+            got = g.attend(st)                              # same cache, plain decode
+            assert report_err(f"{w.name} fuse={fuse} step", got_step, want) <= TOL
+            assert report_err(f"{w.name} fuse={fuse}", got, want) <= TOL
+            outs.setdefault(fuse, []).append(got)
+        assert np.array_equal(outs[2][0], outs[2][1])
+        a, b = W.bf16_bits_to_f64(outs[2][0]), W.bf16_bits_to_f64(outs[1][0])
+        assert np.abs(a - b).max() <= 2.0 ** -7 * max(1.0, np.abs(b).max())   # same partials, other summation order
+        # with empty sequences in the batch (length 0: an all-zero row, no partial with keys)
+        sp.sp_debug_set_tuning("decode_fuse", 2)
+        q = to_dev(st.q)
+        out = torch.full_like(q, 7.0)
+        sl = st.seq_lens.copy()
+        sl[[1, 4]] = 0
+        mx = int(sl.max())
+        ws = torch.empty(sp.sp_attn_decode_workspace_size(w.batch, mx, Hq, d), dtype=torch.uint8, device="cuda")
+        sp.sp_attn_decode(g.cache, q, out, dev_i32(sl), g.bt, mx, float(w.scale), ws)
+        got = bits_of(out)
+        assert (got[1] == 0).all() and (got[4] == 0).all()
+        want0 = o.o.attn_decode(o.kp, o.vp, st.q, sl, w.block_table, w.scale)
+        assert report_err(f"{w.name} with empty sequences", got, want0) <= TOL
+    finally:
+        sp.sp_debug_set_tuning("decode_chunk", 0)
+        sp.sp_debug_set_tuning("decode_fuse", 0)
 
 
 @pytest.mark.parametrize("ring", [1, 2, 3, 4])
