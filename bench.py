@@ -468,9 +468,12 @@ def extra_mixed_batch(sp, iters=30):
     need_a = sp.sp_attn_prefill_workspace_size(63, T, 1, int(total[:63].max()), 8, 1, 128)
     ws_a = torch.empty(need_a, dtype=torch.uint8, device="cuda") if need_a else None
 
+    need_b = sp.sp_attn_prefill_workspace_size(1, T, 2048, 2048, 8, 1, 128)
+    ws_b = torch.empty(need_b, dtype=torch.uint8, device="cuda") if need_b else None
+
     def two():
         sp.sp_attn_prefill(cache, q, out, cu[:64], cx[:63], bt[:63], 1, int(total[:63].max()), scale, workspace=ws_a)
-        sp.sp_attn_prefill(cache, q, out, cu[63:], cx[63:], bt[63:], 2048, 2048, scale)
+        sp.sp_attn_prefill(cache, q, out, cu[63:], cx[63:], bt[63:], 2048, 2048, scale, workspace=ws_b)
 
     two_t = time_one(two, iters)
     flops = 4 * 128 * 8 * int((new.astype(np.int64) * ctx + new.astype(np.int64) * (new + 1) // 2).sum())

@@ -118,9 +118,12 @@ int sp_kv_append(const sp_cache_desc *cache, const void *k_new, const void *v_ne
  * total_q_tokens, advance cu_seqlens_q, ctx_lens and block_table to the first sequence of the
  * range and pass the range's batch size and hints (cu_seqlens_q keeps its absolute token
  * offsets).
- * A mixed batch — single-token sequences plus prefill chunks in one step — is best served
- * that way, the short sequences in one call and the chunks in another (or sp_attn_decode for
- * the former): each part then gets the kernel and the launch shape that suit it.
+ * Mixed batches — sequences with a few query tokens (single-token decodes, verification chunks)
+ * next to sequences with long prefill chunks in one step — are served by one call: given the
+ * workspace, the library routes the short sequences (at most 32 / (query heads per KV head)
+ * tokens) to the decode kernels and the others to the prefill kernel, by the lengths it finds
+ * on the device.  It takes a batch for mixed when the hints say so: max_q_len beyond that token
+ * count, and total_q_tokens - max_q_len smaller than (batch - 1) times that count plus one.
  * Arithmetic: bf16 MFMA with fp32 accumulation, fp32 online softmax.  The error bound of
  * 1e-2 absolute against the exact result holds for inputs distributed like N(0,1) q, k, v with
  * scale 1/sqrt(head_dim); it scales with |out| (bf16 output: half an ulp is 2^-9 |out|) and,

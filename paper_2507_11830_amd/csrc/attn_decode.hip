@@ -36,6 +36,8 @@ struct DecodeArgs {
   float *part_ml;  // [row][nsplit][2]  (m in log2 units, l)
   int max_pages, num_pages, Hq, Hkv, group, geff, n_hgroups, chunk, nsplit;
   int q_cap;  // MQ kernels: query tokens per tile (32 / geff)
+  int route_cap;  // MQ kernels: 0, or (mixed batches) only sequences with at most this many query tokens are
+                  // served, and the partials are indexed [sequence][route_cap tokens][head] instead of by token row
   int32_t *arrive;  // FUSE kernels: one arrival counter per (sequence, head group), zero between launches
   char *out;        // FUSE kernels: bf16 [batch][Hq][D]
   float sl2e;
@@ -258,12 +260,13 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
   // Column -> (query token, head) of the tile, and the row of q / out / the partials it stands for.
   int L, ctx = 0, kv_end, lim_min = 0, lim_col[NT];
   bool col_valid[NT];
-  long row_col[NT];
+  long row_col[NT], prow_col[NT];  // row of q / out, and row of the partials (the same unless routed)
   if (MQ) {
     const int tok0 = a.cu_q[seq];
     const int qn = a.cu_q[seq + 1] - tok0;
     ctx = a.ctx_lens[seq];
     if (qn <= 0) return;  // no query token: no output row, no partial
+    if (a.route_cap > 0 && qn > a.route_cap) return;  // mixed batch: the prefill kernel serves this sequence
     L = ctx + qn;
     kv_end = L;          // keys visible to the chunk's last token
     lim_min = ctx + 1;   // keys visible to its first token
@@ -273,11 +276,13 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
       const int t = nt * a.q_cap + t0;  // tile nt holds the tokens nt * q_cap .. (nt + 1) * q_cap - 1
       col_valid[nt] = t0 < a.q_cap && t < qn && h_col < ncols;
       row_col[nt] = (long)(tok0 + t) * a.Hq + head0 + h_col;
+      prow_col[nt] = a.route_cap > 0 ? ((long)seq * a.route_cap + t) * a.Hq + head0 + h_col : row_col[nt];
       lim_col[nt] = col_valid[nt] ? ctx + t + 1 : kv_end;
     }
   } else {
     col_valid[0] = col < ncols;
     row_col[0] = (long)seq * a.Hq + head0 + col;
+    prow_col[0] = row_col[0];
     lim_col[0] = 0;
     L = 0;  // loaded below, after the query rows are requested
     kv_end = 0;
@@ -313,7 +318,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
       if (lane < 32 && col_valid[nt])
-        *reinterpret_cast<f32x2 *>(a.part_ml + (row_col[nt] * a.nsplit + split) * 2) = (f32x2){-INFINITY, 0.f};
+        *reinterpret_cast<f32x2 *>(a.part_ml + (prow_col[nt] * a.nsplit + split) * 2) = (f32x2){-INFINITY, 0.f};
     if (FUSE) arrive_and_merge<D>(a, lane, seq, head0, ncols);
     return;
   }
@@ -605,7 +610,7 @@ __global__ __launch_bounds__(64, NT > 1 ? 1 : 2) void decode_split_kernel(Decode
   for (int nt = 0; nt < NT; ++nt) {
     const float lt = l[nt] + other_half(l[nt]);
     if (col_valid[nt]) {
-      const long pidx = row_col[nt] * a.nsplit + split;
+      const long pidx = prow_col[nt] * a.nsplit + split;
       float *po = a.part_o + pidx * D;
 #pragma unroll
       for (int db = 0; db < G::kDBlocks; ++db)
@@ -657,25 +662,35 @@ template <int D, int NB, int SPW>
 __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ part_o,
                                                      const float *__restrict__ part_ml,
                                                      char *__restrict__ out, int nsplit,
-                                                     const int32_t *__restrict__ cu_q, int batch, int Hq) {
+                                                     const int32_t *__restrict__ cu_q, int batch, int Hq, int route_cap) {
   // SPW = slices per wave: 1, or all D / 32 slices of the row when there are so many rows that
   // the launch would otherwise be tens of thousands of waves that each wait one round trip for
   // half a KiB (the weights are then computed once per row instead of once per slice).
   constexpr int SL = D / 32;  // slices per row
   static_assert(SPW == 1 || SPW == SL, "a wave takes one slice or the whole row");
-  const long row = SPW == 1 ? blockIdx.x / SL : blockIdx.x;
+  const long row = SPW == 1 ? blockIdx.x / SL : blockIdx.x;  // row of the partials
   const int sl0 = SPW == 1 ? (int)(blockIdx.x - row * SL) : 0;
   const int lane = threadIdx.x;
   const int g = lane >> 3, ch = sl0 * 32 + (lane & 7) * 4;
-  char *dst = out + (row * D + ch) * 2;  // slice p of the wave: + 64 p bytes
   // Rows of a varlen batch: only those of this call's sequences are written (a call on a
   // sub-range of a batch's sequences must leave the other rows of `out` alone).  Requested with
   // everything else, looked at only before the store.
-  long row_lo = 0, row_hi = 0x7fffffffffffffffL;
-  if (cu_q != nullptr) {
+  long row_lo = 0, row_hi = 0x7fffffffffffffffL, orow = row;
+  if (route_cap > 0) {
+    // Mixed batch: the partials are indexed [sequence][route_cap tokens][head]; the output row of
+    // (sequence, token) follows from the sequence's first query token, and only sequences with at
+    // most route_cap query tokens have partials at all.
+    const int seq = (int)(row / ((long)route_cap * Hq));
+    const int rem = (int)(row - (long)seq * route_cap * Hq);
+    const int t = rem / Hq, head = rem - t * Hq;
+    const int q0 = cu_q[seq], qn = cu_q[seq + 1] - q0;
+    orow = (long)(q0 + t) * Hq + head;
+    if (t >= qn || qn > route_cap) row_hi = -1;  // no such row: nothing is stored
+  } else if (cu_q != nullptr) {
     row_lo = (long)cu_q[0] * Hq;
     row_hi = (long)cu_q[batch] * Hq;
   }
+  char *dst = out + (orow * D + ch) * 2;  // slice p of the wave: + 64 p bytes
   if (part_o == nullptr) {  // every sequence of the batch is empty
 #pragma unroll
     for (int p = 0; p < SPW; ++p)
@@ -731,7 +746,7 @@ __global__ __launch_bounds__(64) void combine_kernel(const float *__restrict__ p
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[p][j] += __shfl_xor(acc[p][j], o);
   }
-  if (g != 0 || row < row_lo || row >= row_hi) return;
+  if (g != 0 || orow < row_lo || orow >= row_hi) return;
   const float inv = M == -INFINITY ? 0.f : 1.0f / den;  // a row without keys: zeros
 #pragma unroll
   for (int p = 0; p < SPW; ++p)
@@ -743,7 +758,7 @@ static thread_local int g_combine_rows_per_wave = 0;  // tuning hook: 0 heuristi
 void set_combine_form(int form) { g_combine_rows_per_wave = form; }
 
 int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
-                   hipStream_t stream, const int32_t *cu_q, int batch, int num_q_heads) {
+                   hipStream_t stream, const int32_t *cu_q, int batch, int num_q_heads, int route_cap) {
   if (rows <= 0) return SP_OK;
   const int nb = nsplit <= 32 ? 4 : nsplit <= 64 ? 8 : nsplit <= 128 ? 16 : 32;  // >= ceil(nsplit / 8) up to 256 splits
   const int sl = head_dim / 32;
@@ -756,7 +771,7 @@ int launch_combine(const float *part_o, const float *part_ml, void *out, long ro
   char *o = (char *)out;
 #define SP_COMBINE(D_, NB_, SPW_) \
   hipLaunchKernelGGL((combine_kernel<D_, NB_, SPW_>), grid, dim3(64), 0, stream, part_o, part_ml, o, nsplit, cu_q, batch, \
-                     num_q_heads)
+                     num_q_heads, route_cap)
   if (head_dim == 128) {
     if (whole && nb == 4) SP_COMBINE(128, 4, 4);
     else if (whole) SP_COMBINE(128, 8, 4);
@@ -891,18 +906,51 @@ size_t decode_multi_workspace_bytes(int batch, int total_q, int max_q_len, int m
   return (size_t)total_q * num_q_heads * nsplit * (head_dim + 2) * sizeof(float);
 }
 
+// Mixed batches (sequences with a few query tokens next to sequences with long chunks, the usual
+// step of a continuous-batching scheduler): the short ones are served by the split kernel, which
+// skips the others, with partials indexed [sequence][cap tokens][head].  cap = the tokens one
+// column tile holds; 0 if the head configuration has no such form.
+int decode_route_cap(int num_q_heads, int num_kv_heads) {
+  DecodeArgs a;
+  set_head_groups(a, num_q_heads, num_kv_heads);
+  return a.q_cap;
+}
+
+size_t decode_routed_workspace_bytes(int batch, int max_kv_len, int num_q_heads, int num_kv_heads, int head_dim) {
+  DecodeArgs a;
+  set_head_groups(a, num_q_heads, num_kv_heads);
+  if (max_kv_len <= 0 || batch <= 0 || (long)batch * a.n_hgroups > 65535) return 0;
+  const int chunk = pick_chunk(batch, num_q_heads, max_kv_len, a.q_cap);
+  const size_t nsplit = (size_t)(max_kv_len + chunk - 1) / chunk;
+  return (size_t)batch * a.q_cap * num_q_heads * nsplit * (head_dim + 2) * sizeof(float);
+}
+
 // Returns SP_OK after launching, or 1 when the shape or the workspace does not qualify (the caller
-// then runs the general prefill kernel).
+// then runs the general prefill kernel).  routed: serve only the sequences with at most
+// decode_route_cap query tokens (the caller's other kernel serves the rest).
 int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
                         const int32_t *cu_q,
                         const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                         int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
-                        void *workspace, size_t workspace_bytes, hipStream_t stream) {
-  const size_t need = decode_multi_workspace_bytes(batch, total_q, max_q_len, max_kv_len, num_q_heads,
-                                                   c.num_kv_heads, c.head_dim);
-  if (need == 0 || !workspace || workspace_bytes < need) return 1;
+                        void *workspace, size_t workspace_bytes, hipStream_t stream, bool routed) {
   DecodeArgs a;
-  const int tiles = multi_shape(batch, max_q_len, num_q_heads, c.num_kv_heads, &a);
+  int tiles;
+  size_t need;
+  long prows;
+  if (routed) {
+    need = decode_routed_workspace_bytes(batch, max_kv_len, num_q_heads, c.num_kv_heads, c.head_dim);
+    set_head_groups(a, num_q_heads, c.num_kv_heads);
+    tiles = 1;
+    a.route_cap = a.q_cap;
+    max_q_len = a.q_cap;
+    prows = (long)batch * a.q_cap * num_q_heads;
+  } else {
+    need = decode_multi_workspace_bytes(batch, total_q, max_q_len, max_kv_len, num_q_heads, c.num_kv_heads, c.head_dim);
+    tiles = multi_shape(batch, max_q_len, num_q_heads, c.num_kv_heads, &a);
+    a.route_cap = 0;
+    prows = (long)total_q * num_q_heads;
+  }
+  if (need == 0 || !workspace || workspace_bytes < need) return 1;
   a.k_pages = (const char *)c.k_pages;
   a.v_pages = (const char *)c.v_pages;
   a.k_new = (const char *)k_new;  // both NULL: the chunk's rows are in the cache already
@@ -921,7 +969,7 @@ int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v
   a.chunk = pick_chunk(batch, num_q_heads, max_kv_len, max_q_len);
   a.nsplit = (max_kv_len + a.chunk - 1) / a.chunk;
   a.part_o = (float *)workspace;
-  a.part_ml = a.part_o + (size_t)total_q * num_q_heads * a.nsplit * c.head_dim;
+  a.part_ml = a.part_o + (size_t)prows * a.nsplit * c.head_dim;
   int rc;
   if (k_new) {  // fused append of the chunk's rows
     if (tiles == 1)
@@ -940,8 +988,7 @@ int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v
   if (rc != SP_OK) return rc;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SP_ERR_HIP, "short-chunk split launch: %s", hipGetErrorString(e));
-  return launch_combine(a.part_o, a.part_ml, out, (long)total_q * num_q_heads, a.nsplit, c.head_dim, stream, cu_q, batch,
-                        num_q_heads);
+  return launch_combine(a.part_o, a.part_ml, out, prows, a.nsplit, c.head_dim, stream, cu_q, batch, num_q_heads, a.route_cap);
 }
 
 int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, const void *q, void *out,
@@ -958,6 +1005,7 @@ int launch_decode(const sp_cache_desc &c, const void *k_new, const void *v_new, 
   a.seq_lens = seq_lens;
   a.arrive = nullptr;
   a.out = nullptr;
+  a.route_cap = 0;
   a.cu_q = a.ctx_lens = nullptr;
   a.block_table = block_table;
   a.max_pages = max_pages;

@@ -64,6 +64,7 @@ struct PrefillArgs {
   int total_q;     // host count of query tokens (bounds the number of work items)
   int ranked;      // workgroups take their work items heaviest first (ranked_item below)
   int rank_shift;  // log2 of the weight unit in keys
+  int route_cap;   // mixed batches: sequences with at most this many query tokens belong to the split kernel (0: none)
 };
 
 // Inclusive prefix sum over the 64 lanes (gfx9 DPP: shifts inside rows of 16, then the two row
@@ -124,6 +125,7 @@ __device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift,
       const int q0 = a.cu_q[s];
       qs[u] = q0;
       q[u] = max(a.cu_q[s + 1] - q0, 0);
+      if (q[u] <= a.route_cap) q[u] = 0;  // served by the split kernel (route_cap = 0: nothing is)
       c[u] = max(a.ctx_lens[s], 0);
       nt[u] = (q[u] + tpt - 1) >> tpt_shift;
     }
@@ -292,6 +294,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     q0 = a.cu_q[seq];
     q_len = a.cu_q[seq + 1] - q0;
     ctx = a.ctx_lens[seq];
+    if (q_len <= a.route_cap) return;  // mixed batch: the split kernel serves this sequence
   }
   const int tok0 = tile * tpt;
   if (tok0 >= q_len) return;
@@ -803,14 +806,30 @@ static int kv_split_cap(long rows) {
   return (int)(cap < 1 ? 1 : cap > kMaxKvSplits ? kMaxKvSplits : cap);
 }
 
+// Mixed batch?  Decided from the host-side hints alone: chunks too long for the short-chunk path
+// exist (max_q_len), and the tokens besides the longest chunk are so few that at least one other
+// sequence must be short — those sequences are then routed to the split kernel (which reads a
+// long cached prefix once, in pieces, at memory speed) and the rest to the prefill kernel, inside
+// the one call.  Returns the token bound of "short" (one column tile of the split kernel), or 0.
+static int mixed_route_cap(int batch, int total_q, int max_q_len, int num_q_heads, int num_kv_heads) {
+  if (g_short_chunk_mode == 1 || batch < 2) return 0;
+  const int cap = decode_route_cap(num_q_heads, num_kv_heads);
+  if (cap <= 0 || max_q_len <= cap) return 0;  // no long chunk: the whole batch takes the short-chunk path
+  const long rest = (long)total_q - max_q_len;
+  if (rest <= 0 || rest >= (long)(batch - 1) * (cap + 1)) return 0;
+  return cap;
+}
+
 size_t prefill_workspace_bytes(int batch, int total_q_tokens, int max_q_len, int max_kv_len, int num_q_heads,
                                int num_kv_heads, int head_dim) {
   const long rows = (long)total_q_tokens * num_q_heads;
   const int cap = kv_split_cap(rows);
   const size_t pieces = cap >= 2 ? (size_t)rows * cap * (head_dim + 2) * sizeof(float) : 0;
-  const size_t shortq = g_short_chunk_mode == 1 ? 0
-                                                : decode_multi_workspace_bytes(batch, total_q_tokens, max_q_len, max_kv_len,
-                                                                               num_q_heads, num_kv_heads, head_dim);
+  size_t shortq = g_short_chunk_mode == 1 ? 0
+                                          : decode_multi_workspace_bytes(batch, total_q_tokens, max_q_len, max_kv_len,
+                                                                         num_q_heads, num_kv_heads, head_dim);
+  if (mixed_route_cap(batch, total_q_tokens, max_q_len, num_q_heads, num_kv_heads) > 0)
+    shortq = decode_routed_workspace_bytes(batch, max_kv_len, num_q_heads, num_kv_heads, head_dim);
   return pieces > shortq ? pieces : shortq;
 }
 
@@ -938,6 +957,18 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
     if ((size_t)kvs > fit) kvs = (int)fit;
     if (kvs < 1) kvs = 1;
   }
+  // Mixed batch: short sequences go to the split kernel (launched last, below) when the workspace
+  // holds their partials; the prefill kernel then skips them, and its key ranges stay uncut (the
+  // longest key range of the batch, which sizes the pieces, belongs to a short sequence as a rule).
+  a.route_cap = 0;
+  {
+    const int cap = mixed_route_cap(batch, total_q, max_q_len, num_q_heads, c.num_kv_heads);
+    const size_t need = cap > 0 ? decode_routed_workspace_bytes(batch, max_kv_len, num_q_heads, c.num_kv_heads, c.head_dim) : 0;
+    if (need > 0 && workspace && workspace_bytes >= need) {
+      a.route_cap = cap;
+      if (g_kv_splits == 0) kvs = 1;
+    }
+  }
   a.kv_splits = kvs;
   // Heaviest-first dispatch when the static (tile, sequence) order is not already that: several
   // sequences with cached prefixes (without prefixes the last query tiles of all sequences are
@@ -954,8 +985,19 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   const bool split = small_grid || kvs > 1;
   int rc = c.head_dim == 128 ? launch_prefill_d<128>(a, split, batch, max_q_len, stream)
                              : launch_prefill_d<64>(a, split, batch, max_q_len, stream);
-  if (rc != SP_OK || kvs == 1) return rc;
-  return launch_combine(a.part_o, a.part_ml, out, rows, kvs, c.head_dim, stream, cu_q, batch, num_q_heads);
+  if (rc != SP_OK) return rc;
+  if (kvs > 1) {
+    rc = launch_combine(a.part_o, a.part_ml, out, rows, kvs, c.head_dim, stream, cu_q, batch, num_q_heads);
+    if (rc != SP_OK) return rc;
+  }
+  if (a.route_cap > 0) {
+    // ... and the short sequences of a mixed batch on the split kernel, in the same stream: it runs
+    // after the launches above, so it may reuse the workspace, and its rows are its own.
+    rc = launch_decode_multi(c, nullptr, nullptr, q, out, cu_q, ctx_lens, block_table, batch, max_pages, total_q, max_q_len,
+                             max_kv_len, num_q_heads, scale, workspace, workspace_bytes, stream, true);
+    if (rc == 1) return fail(SP_ERR_WORKSPACE, "sp_attn_prefill: workspace too small for the routed short sequences");
+  }
+  return rc;
 }
 
 }  // namespace sp

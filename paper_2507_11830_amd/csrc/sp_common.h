@@ -59,8 +59,10 @@ void set_prefill_order(int mode);  // 0 heuristic, 1 workgroups in (tile, sequen
 // part_ml [rows][nsplit][2] fp32 (max in log2 units, sum); out [rows][head_dim] bf16.
 // part_o == nullptr writes zero rows.
 // cu_q non-NULL (varlen batches): only the rows [cu_q[0], cu_q[batch]) x num_q_heads are written.
+// route_cap > 0 (mixed batches): the partials' rows are [sequence][route_cap tokens][head] (see launch_decode_multi).
 int launch_combine(const float *part_o, const float *part_ml, void *out, long rows, int nsplit, int head_dim,
-                   hipStream_t stream, const int32_t *cu_q = nullptr, int batch = 0, int num_q_heads = 0);
+                   hipStream_t stream, const int32_t *cu_q = nullptr, int batch = 0, int num_q_heads = 0,
+                   int route_cap = 0);
 
 size_t decode_workspace_bytes(int batch, int max_seq_len, int num_q_heads, int head_dim);
 // k_new / v_new non-NULL: fused decode step (the new token's rows are appended by the kernel).
@@ -86,6 +88,10 @@ int launch_decode_multi(const sp_cache_desc &c, const void *k_new, const void *v
                         const int32_t *cu_q,
                         const int32_t *ctx_lens, const int32_t *block_table, int batch, int max_pages,
                         int total_q, int max_q_len, int max_kv_len, int num_q_heads, float scale,
-                        void *workspace, size_t workspace_bytes, hipStream_t stream);
+                        void *workspace, size_t workspace_bytes, hipStream_t stream, bool routed = false);
+// Mixed batches: routed = true serves only the sequences with at most decode_route_cap query tokens
+// (partials indexed [sequence][cap][head]; workspace size from decode_routed_workspace_bytes).
+int decode_route_cap(int num_q_heads, int num_kv_heads);
+size_t decode_routed_workspace_bytes(int batch, int max_kv_len, int num_q_heads, int num_kv_heads, int head_dim);
 
 }  // namespace sp

@@ -835,6 +835,45 @@ def test_mixed_batch_split_into_two_calls():
     assert report_err("mixed batch in two calls", bits_of(out), want) <= TOL
 
 
+MIXED_CASES = {
+    # name: (Hq, Hkv, d, new tokens per sequence, cached tokens per sequence)
+    # single-token sequences and chunks in one batch; 4 tokens still fit the split kernel's column
+    # tile at 8 heads per KV head, 5 do not
+    "decodes+chunk": (8, 1, 128, [1, 1, 1, 1, 1, 1, 300, 1], [700, 33, 4000, 2049, 15, 0, 100, 1500]),
+    "cap-boundary": (8, 1, 128, [4, 5, 1, 0, 4, 600, 2, 3], [1000, 1000, 77, 50, 0, 0, 3333, 4095]),
+    "two-chunks": (8, 1, 128, [1, 257, 1, 1, 1, 512, 1, 1, 1, 1], [5000, 300, 129, 64, 8191, 1024, 1, 2, 3, 4]),
+    "g4-8b": (32, 8, 128, [8, 1, 9, 400, 2], [700, 2049, 64, 130, 999]),
+    "d64": (8, 2, 64, [1, 1, 130, 1], [333, 1025, 200, 0]),
+    "chunk-first": (8, 1, 128, [700, 1, 1, 1], [0, 900, 901, 902]),
+}
+
+
+@pytest.mark.parametrize("case", sorted(MIXED_CASES))
+def test_mixed_batch_in_one_call(case):
+    """A continuous-batching step — sequences with a few query tokens next to sequences with long
+    chunks — in ONE sp_attn_prefill call: with a workspace the library serves the short sequences
+    on the split kernel and the others on the prefill kernel.  Every output row against the oracle;
+    the same through sp_chunk_step (cache image too); rows of `out` outside the batch untouched."""
+    import torch
+    import paper_2507_11830_amd as sp
+
+    Hq, Hkv, d, new, ctx = MIXED_CASES[case]
+    new, ctx = np.array(new), np.array(ctx)
+    w = custom_workload(f"mixed-{case}", ctx + new, ctx, Hq, Hkv, d, "prefill", seed=141)
+    total, mq, mkv = int(new.sum()), int(new.max()), int((ctx + new).max())
+    need = sp.sp_attn_prefill_workspace_size(len(new), total, mq, mkv, Hq, Hkv, d)
+    assert need > 0                                  # the hints identify the batch as mixed
+    run_full_compare(w)
+    run_chunk_steps(w)
+    # a too small workspace only changes the launch shape, not the result
+    g, o = GpuRunner(w), OracleRunner(w)
+    g.prefill_workspace = False
+    for st in w.steps():
+        g.append(st)
+        o.append(st)
+    assert report_err(f"{w.name} without workspace", g.attend(st), o.attend(st)) <= TOL
+
+
 def test_chunk_step_in_a_hip_graph():
     """The same for sp_chunk_step on a verification batch (append fused into the attention launch):
     captured once, replayed with stale workspace and output contents, every replay equal to the
