@@ -442,6 +442,48 @@ def test_other_shard_shapes_of_the_sp_tp_family(Hq, Hkv):
     run_full_compare(custom_workload(f"shape-d-{Hq}-{Hkv}", lens, lens - 1, Hq, Hkv, 128, "decode", seed=52))
 
 
+@pytest.mark.parametrize("Hq,Hkv,d", [(16, 2, 128), (32, 4, 128), (64, 8, 128), (32, 8, 128), (16, 2, 64)])
+def test_other_shard_shapes_at_scale(Hq, Hkv, d):
+    """The same shapes with sequences of several thousand tokens, so that the launches take the
+    forms they take at full scale: 256-column workgroups with shared key tiles, a multiple of 8
+    (sequence, head group) streams pinned to XCDs, many query tiles per stream, cached prefixes;
+    then a decode step with several splits per sequence.  Every element against the oracle."""
+    new = np.array([3000, 1100, 2049, 0, 4096 if Hq <= 32 else 1500])
+    ctx = np.array([1000, 0, 300, 77, 0])
+    run_full_compare(custom_workload(f"scale-p-{Hq}-{Hkv}-{d}", ctx + new, ctx, Hq, Hkv, d, "prefill", seed=151), check_cache=False)
+    lens = np.array([5000, 2049, 777, 1, 4096, 3001, 129, 6000])
+    run_full_compare(custom_workload(f"scale-d-{Hq}-{Hkv}-{d}", lens, lens - 1, Hq, Hkv, d, "decode", seed=152), check_cache=False)
+
+
+def test_tolerance_margin_on_rows_of_moderate_length():
+    """Where the 1e-2 bound is tightest: rows with few enough keys that the bf16 rounding of the
+    weights does not average out, and outputs of magnitude >= 2, whose own bf16 rounding is up to
+    0.0078.  Rows of up to 256 keys take their weights as hi + lo, so their error must stay at
+    the output's half ulp; rows of 257..1024 keys must keep 15 % headroom under the bound.  Many
+    short sequences, so that thousands of such rows (and a few hundred elements >= 2) occur."""
+    rng = np.random.default_rng(161)
+    new = rng.integers(200, 1025, size=24)
+    ctx = np.where(rng.random(24) < 0.5, 0, rng.integers(0, 300, size=24))
+    w = custom_workload("margin", ctx + new, ctx, 8, 1, 128, "prefill", seed=162)
+    g, o = GpuRunner(w), OracleRunner(w)
+    for st in w.steps():
+        g.append(st)
+        o.append(st)
+    got, want = W.bf16_bits_to_f64(g.attend(st)), o.attend(st)
+    err = np.abs(got - want)
+    keys = np.concatenate([np.arange(c + 1, c + n + 1) for c, n in zip(st.ctx_lens, st.new_lens)])   # visible keys per token row
+    half_ulp = 2.0 ** -8 * 2.0 ** np.floor(np.log2(np.maximum(np.abs(want), 2.0 ** -126)))   # bf16: 8 significant bits
+    short, mid = keys <= 256, (keys > 256) & (keys <= 1024)
+    big = np.abs(want) >= 2.0
+    print(f"[margin] rows <= 256 keys: {short.sum()}, elements >= 2 there: {(big & short[:, None, None]).sum()}, "
+          f"max err {err[short].max():.5f}; rows 257..1024: {mid.sum()}, elements >= 2: {(big & mid[:, None, None]).sum()}, "
+          f"max err {err[mid].max():.5f}", flush=True)
+    assert (big & short[:, None, None]).sum() > 0
+    # hi + lo rows: the output's own rounding plus fp32 accumulation noise
+    assert (err[short] <= half_ulp[short] * 1.02 + 2e-4).all()
+    assert err[mid].max() <= 0.85e-2 and err.max() <= TOL
+
+
 def test_short_query_chunks_on_long_prefixes():
     """Speculative-verification shape: 2-8 query tokens per sequence against a long cached prefix,
     causal inside the chunk, served by sp_attn_prefill on the same cache."""
