@@ -39,8 +39,8 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by
 # what the same counters read for the 1 GiB copy of `--workload copy` (FETCH_SIZE x2.000,
 # WRITE_SIZE x1.000); figures and commands in profiles/pmc_hbm_traffic_and_mfma.md.
-TRAFFIC_PREFILL_C5A = int(323826.6 * 1024 * 2.0 + 65536.3 * 1024)
-TRAFFIC_DECODE_C3 = int((68030.6 + 3666.5) * 1024 * 2.0 + (3892.0 + 128.0) * 1024)
+TRAFFIC_PREFILL_C5A = int(359105.0 * 1024 * 2.0 + 65852.2 * 1024)
+TRAFFIC_DECODE_C3 = int((68028.5 + 3678.5) * 1024 * 2.0 + (3889.6 + 128.0) * 1024)
 
 
 def _dev_bf16(u16):

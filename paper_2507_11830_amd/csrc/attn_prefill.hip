@@ -49,6 +49,26 @@ __device__ __forceinline__ void sgb_steady() {
   }
 }
 
+// Measurement switches (compile-time, all off in the product build; the profiles record what each
+// costs): -DSP_PREFILL_ALWAYS_FULL computes the tile max in every tile (the full softmax pass
+// everywhere), -DSP_PREFILL_SUM_DOT2 sums the bf16-rounded weight pairs with the dot-product
+// instruction instead of adding the fp32 weights, -DSP_PREFILL_SUM_MFMA sums them with 4x4x4
+// MFMAs against an all-ones operand, -DSP_PREFILL_PRIO raises the wave priority during the
+// matrix phases.  (Both alternative sums go through the matrix pipe, where they queue behind the
+// other wave's 32-cycle MFMAs: a third more cycles for the whole kernel.)
+#ifdef SP_PREFILL_PRIO
+#define SP_MATRIX_PHASE_BEGIN() __builtin_amdgcn_s_setprio(3)
+#define SP_MATRIX_PHASE_END() __builtin_amdgcn_s_setprio(0)
+#else
+#define SP_MATRIX_PHASE_BEGIN()
+#define SP_MATRIX_PHASE_END()
+#endif
+#ifdef SP_PREFILL_ALWAYS_FULL
+constexpr bool kAlwaysFullSoftmax = true;
+#else
+constexpr bool kAlwaysFullSoftmax = false;
+#endif
+
 struct PrefillArgs {
   const char *k_pages, *v_pages, *q;
   char *out;
@@ -549,10 +569,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
         }
     }
     float lsum = 0.f;
-    bool full = FIRST || keep_fp32;
+    bool full = FIRST || keep_fp32 || kAlwaysFullSoftmax;
     if (!full) {
       const float msc = m_used * a.sl2e;
       float ls0 = 0.f, ls1 = 0.f;
+#ifdef SP_PREFILL_SUM_MFMA
+      f32x4 lacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#endif
 #pragma unroll
       for (int b = 0; b < KB; ++b)
 #pragma unroll
@@ -566,12 +589,34 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
             const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i], a.sl2e, -msc));
             const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i + 1], a.sl2e, -msc));
             u.h[i] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+#if defined(SP_PREFILL_SUM_DOT2)
+            ls0 = __builtin_amdgcn_fdot2_f32_bf16(u.h[i], (bf16x2){(__bf16)1.0f, (__bf16)1.0f}, ls0, false);
+#elif !defined(SP_PREFILL_SUM_MFMA)
             ls0 += p0;
             ls1 += p1;
+#endif
           }
           pop[b][ks] = u.v;
+#ifdef SP_PREFILL_SUM_MFMA
+          {
+            // row sums on the matrix pipe: a 4x4x4 MFMA (16 blocks) with an all-ones A operand adds up
+            // the four bf16 values each lane holds in B; two of them cover this operand's eight
+            union {
+              bf16x8 v;
+              s16x4 q[2];
+            } w;
+            w.v = u.v;
+            const s16x4 ones4 = {0x3F80, 0x3F80, 0x3F80, 0x3F80};
+            lacc[ks] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones4, w.q[0], lacc[ks], 0, 0, 0);
+            lacc[ks] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones4, w.q[1], lacc[ks], 0, 0, 0);
+          }
+#endif
         }
+#ifdef SP_PREFILL_SUM_MFMA
+      lsum = lacc[0][0] + lacc[1][0];
+#else
       lsum = ls0 + ls1;
+#endif
       // NaN (a masked score against a running max that is still -inf) must take the full pass too
       full = __builtin_amdgcn_ballot_w64(!(lsum <= 256.0f)) != 0;  // wave-uniform, rare
     }
@@ -678,7 +723,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
         constexpr int PAR = decltype(parc)::value;
         if (PREC && precise(t - 1)) pv_residual(integral_constant<int, 1 - PAR>{});  // V(t-1) became visible at the barrier
         issue_prep(t, parc);
+        SP_MATRIX_PHASE_BEGIN();
         pv_qk(true_type{}, parc);
+        SP_MATRIX_PHASE_END();
         softmax(t, false_type{}, PREC && precise(t));
         wait_loads();
         __syncthreads();
@@ -704,7 +751,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
         auto period = [&](int t, auto parc) __attribute__((always_inline)) {
           constexpr int PAR = decltype(parc)::value;
           if (PREC && precise(t - 1)) pv_residual(integral_constant<int, 1 - PAR>{});
+          SP_MATRIX_PHASE_BEGIN();
           pv_qk(false_type{}, parc);
+          SP_MATRIX_PHASE_END();
           __syncthreads();
           softmax(t, false_type{}, PREC && precise(t));
         };
