@@ -13,12 +13,13 @@
 //
 // Bound: bf16 MFMA (4 * head_dim flops per visible (query, key) pair per head).  K/V HBM
 // traffic is ~1/(8*columns) of that in bytes and is served mostly from L2.  Next to the matrix
-// pipe the kernel keeps the VALU (softmax: about 5.5 instructions per MFMA, the exponential at
-// half rate) and LDS (every MFMA takes one 1 KiB operand from it) busy at the same time;
-// measured on a 32 k-token prefill the matrix pipe is busy in about 70 % of the cycles, the
-// VALU in about 60 %, LDS in about 35 %, and taking the softmax or the LDS reads out
-// altogether gains only about 10 % each: no single unit is the bottleneck, the structure below
-// is about keeping all of them going at once.
+// pipe the kernel keeps the VALU (softmax: 3.5 instructions per score, the exponential at half
+// rate) and LDS (every MFMA takes one 1 KiB operand from it) busy at the same time.  Measured on
+// a 32 k-token prefill, the number of VALU instructions decides the cycle count (one more
+// instruction per score costs a quarter more cycles), so the softmax is a single pass without a
+// tile max and the matrix phases carry no address arithmetic; the matrix pipe is then busy in
+// about 85 % of the cycles a CU is busy, and what limits the kernel beyond that is the clock the
+// chip grants under this load.
 #include <type_traits>
 
 #include "attn_tile.h"
@@ -234,7 +235,7 @@ __device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift,
 // harmless in fp32/bf16) and the O accumulators need no rescale.
 //
 // SPLIT = false is the arrangement described above: the groups own neighbouring sets of 128
-// columns and share every K/V tile (the first group brings in K, the second V).  SPLIT = true
+// columns and share every K/V tile (the first group issues all tile loads).  SPLIT = true
 // is for small grids, where a few hundred workgroups with a triangular causal profile leave
 // most CUs waiting for the one with the longest key range: both groups then own the SAME 128
 // columns and take alternate key tiles (group g the tiles 2i + g, each with its own K and V
@@ -245,7 +246,8 @@ __device__ __forceinline__ bool ranked_item(const PrefillArgs &a, int tpt_shift,
 // PART = true additionally cuts a query tile's key range into kv_splits contiguous pieces, one
 // workgroup each (blockIdx.z), which write un-normalised partials for the combine pass: the way
 // out when a batch has few query tokens on long cached prefixes (late chunks of a chunked
-// prefill), where one workgroup per query tile would walk thousands of keys alone.
+// prefill), where one workgroup per query tile would walk thousands of keys alone.  Only
+// instantiated together with SPLIT (such launches are small grids).
 template <int D, int KVT, int PFD, bool SPLIT, bool PART>
 __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   using G = TileGeom<D>;
