@@ -38,7 +38,7 @@ __device__ __forceinline__ void sgb_prologue() {
     sgb_prologue<I + 1, N, I0, NPV, PFD>();
   }
 }
-template <int I, int N, int I0, int NPV, int PFD>
+template <int I, int N, int I0, int NPV, int PFD, int VPM>
 __device__ __forceinline__ void sgb_steady() {
   if constexpr (I < N) {
     if constexpr (I + PFD < N) {
@@ -46,17 +46,22 @@ __device__ __forceinline__ void sgb_steady() {
       else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    sgb_steady<I + 1, N, I0, NPV, PFD>();
+    // VPM plain VALU instructions ride behind every PV MFMA (the row sums of the weights it multiplies)
+    if constexpr (VPM > 0 && I0 + I < NPV) __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
+    sgb_steady<I + 1, N, I0, NPV, PFD, VPM>();
   }
 }
 
 // Measurement switches (compile-time, all off in the product build; the profiles record what each
 // costs): -DSP_PREFILL_ALWAYS_FULL computes the tile max in every tile (the full softmax pass
-// everywhere), -DSP_PREFILL_SUM_DOT2 sums the bf16-rounded weight pairs with the dot-product
-// instruction instead of adding the fp32 weights, -DSP_PREFILL_SUM_MFMA sums them with 4x4x4
-// MFMAs against an all-ones operand, -DSP_PREFILL_PRIO raises the wave priority during the
-// matrix phases.  (Both alternative sums go through the matrix pipe, where they queue behind the
-// other wave's 32-cycle MFMAs: a third more cycles for the whole kernel.)
+// everywhere); -DSP_PREFILL_SUM_DOT2 sums the bf16-rounded weight pairs with the dot-product
+// instruction and -DSP_PREFILL_SUM_MFMA with 4x4x4 MFMAs against an all-ones operand, instead of
+// adding the fp32 weights (both go through the matrix pipe, where they queue behind the other
+// wave's 32-cycle MFMAs: a third more cycles for the whole kernel); -DSP_PREFILL_SUM_IN_MATRIX_PHASE
+// moves the row sum out of the softmax phase, behind the PV MFMAs of the next matrix phase (unpack
+// the rounded weights by shift / mask, add: four plain VALU instructions per MFMA, which a lone
+// wave hides behind its MFMAs in an issue probe — in this kernel they cost 13 % more time);
+// -DSP_PREFILL_PRIO raises the wave priority during the matrix phases.
 #ifdef SP_PREFILL_PRIO
 #define SP_MATRIX_PHASE_BEGIN() __builtin_amdgcn_s_setprio(3)
 #define SP_MATRIX_PHASE_END() __builtin_amdgcn_s_setprio(0)
@@ -355,7 +360,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // A column of the second SPLIT group may see only masked keys in its first tiles, or none at
   // all: its running max starts at a large finite value so that "all masked" gives weights
   // exp2(-inf) = 0 instead of exp2(-inf + inf).  Tile 0 always holds a visible key otherwise.
-  float m_used = (SPLIT || PART) ? -1e30f : -INFINITY, l = 0.f;
+  float m_used = (SPLIT || PART) ? -1e30f : -INFINITY, l = 0.f, l2 = 0.f;  // row sum in two chains
   f32x16 sacc[KB];
   bf16x8 pop[KB][2];
 
@@ -501,10 +506,26 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     int s = j % G::kDSteps, b = j / G::kDSteps;
     return *(const lds_bf16x8 *)(size_t)(kadr[s] + (unsigned)(KS * TBYTES + 32 * b * ROWB));
   };
+  // Measurement switch SP_PREFILL_SUM_IN_MATRIX_PHASE: the row sum behind the PV MFMAs (unpack the
+  // bf16 weights of 16 / NPV packed registers of P by shift / mask, two chains of adds).
+  constexpr int RPM = (KB * 2 * 4) / NPV;  // packed registers of P per PV MFMA
   auto do_mfma = [&](int i, bf16x8 op) __attribute__((always_inline)) {
     if (i < NPV) {
       int db = i % G::kDBlocks, ks = (i / G::kDBlocks) & 1, b = i / (2 * G::kDBlocks);
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op, pop[b][ks], o[db], 0, 0, 0);
+#ifdef SP_PREFILL_SUM_IN_MATRIX_PHASE
+#pragma unroll
+      for (int e = 0; e < RPM; ++e) {
+        const int pr = i * RPM + e;  // packed register pr of the tile's 16: pop[pr / 8][(pr / 4) & 1], word pr % 4
+        union {
+          bf16x8 v;
+          uint32_t w[4];
+        } u;
+        u.v = pop[pr / 8][(pr / 4) & 1];
+        l += __uint_as_float(u.w[pr % 4] << 16);
+        l2 += __uint_as_float(u.w[pr % 4] & 0xffff0000u);
+      }
+#endif
     } else {
       int j = i - NPV;
       int s = j % G::kDSteps, b = j / G::kDSteps;
@@ -532,8 +553,17 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
         for (int e = 0; e < PER; ++e) issue_emit(i / GAP * PER + e);
       }
     }
+#ifdef SP_PREFILL_SUM_IN_MATRIX_PHASE
+    // the row sums are only read at the very end of the kernel: without a use here the compiler
+    // sinks their adds out of the matrix phase into the softmax that follows
+    if (I0 < NPV) asm volatile("" : "+v"(l), "+v"(l2));
+#endif
     sgb_prologue<0, N, I0, NPV, PFD>();
-    sgb_steady<0, N, I0, NPV, PFD>();
+#ifdef SP_PREFILL_SUM_IN_MATRIX_PHASE
+    sgb_steady<0, N, I0, NPV, PFD, 4 * RPM>();
+#else
+    sgb_steady<0, N, I0, NPV, PFD, 0>();
+#endif
   };
   using slot0 = integral_constant<int, 0>;
   using slot1 = integral_constant<int, 1>;
@@ -574,6 +604,28 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     bool full = FIRST || keep_fp32 || kAlwaysFullSoftmax;
     if (!full) {
       const float msc = m_used * a.sl2e;
+#ifdef SP_PREFILL_SUM_IN_MATRIX_PHASE
+      uint32_t pmax = 0;  // weights are >= 0, so their bit patterns order like their values (and NaN sorts above all)
+#pragma unroll
+      for (int b = 0; b < KB; ++b)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          union {
+            bf16x2 h[4];
+            bf16x8 v;
+          } u;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i], a.sl2e, -msc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i + 1], a.sl2e, -msc));
+            u.h[i] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+            pmax = max(pmax, max(__float_as_uint(p0), __float_as_uint(p1)));  // one v_max3_u32 per pair
+          }
+          pop[b][ks] = u.v;
+        }
+      // NaN (a masked score against a running max that is still -inf) must take the full pass too
+      full = __builtin_amdgcn_ballot_w64(pmax > 0x43800000u) != 0;  // some weight above 2^8: wave-uniform, rare
+#else
       float ls0 = 0.f, ls1 = 0.f;
 #ifdef SP_PREFILL_SUM_MFMA
       f32x4 lacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
@@ -621,6 +673,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 #endif
       // NaN (a masked score against a running max that is still -inf) must take the full pass too
       full = __builtin_amdgcn_ballot_w64(!(lsum <= 256.0f)) != 0;  // wave-uniform, rare
+#endif
     }
     if (full) {
       float mx = sacc[0][0];
@@ -634,6 +687,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
         const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * a.sl2e);
         m_used = m_new;
         l *= alpha;
+        l2 *= alpha;
 #pragma unroll
         for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
@@ -646,7 +700,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           sacc[b][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][r], a.sl2e, -msc));
+#ifndef SP_PREFILL_SUM_IN_MATRIX_PHASE
           lsum += sacc[b][r];
+#endif
         }
         pop[b][0] = pack8(sacc[b], 0);
         pop[b][1] = pack8(sacc[b], 8);
@@ -792,7 +848,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) xch[(16 * db + r) * 256] = o[db][r];
       xch[(NST - 2) * 256] = m_used;
-      xch[(NST - 1) * 256] = l;
+      xch[(NST - 1) * 256] = l + l2;
     }
     __syncthreads();
     if (grp == 1) return;
@@ -800,7 +856,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     const float m_new = fmaxf(m_used, m_b);  // the first group always saw a key: finite
     const float fa = __builtin_amdgcn_exp2f((m_used - m_new) * a.sl2e);
     const float fb = __builtin_amdgcn_exp2f((m_b - m_new) * a.sl2e);  // 0 if the second group had no tile
-    l = l * fa + l_b * fb;
+    l = (l + l2) * fa + l_b * fb;
+    l2 = 0.f;
 #pragma unroll
     for (int db = 0; db < G::kDBlocks; ++db)
 #pragma unroll
@@ -808,6 +865,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     m_used = m_new;  // what l and o now refer to (a partial carries it along)
   }
 
+  l += l2;
   float lt = l + other_half(l);
   if (PART) {  // un-normalised partial for the combine pass
     if (valid) {
