@@ -38,9 +38,9 @@ __device__ __forceinline__ void sgb_prologue() {
     sgb_prologue<I + 1, N, I0, NPV, PFD>();
   }
 }
-template <int I, int N, int I0, int NPV, int PFD, int VPM>
-__device__ __forceinline__ void sgb_steady() {
-  if constexpr (I < N) {
+template <int I, int N, int I0, int NPV, int PFD, int VPM, int NE = N>
+__device__ __forceinline__ void sgb_steady() {  // MFMAs [I, NE) of a sequence of N
+  if constexpr (I < NE) {
     if constexpr (I + PFD < N) {
       if constexpr (I0 + I + PFD < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -48,7 +48,7 @@ __device__ __forceinline__ void sgb_steady() {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     // VPM plain VALU instructions ride behind every PV MFMA (the row sums of the weights it multiplies)
     if constexpr (VPM > 0 && I0 + I < NPV) __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
-    sgb_steady<I + 1, N, I0, NPV, PFD, VPM>();
+    sgb_steady<I + 1, N, I0, NPV, PFD, VPM, NE>();
   }
 }
 
@@ -61,7 +61,12 @@ __device__ __forceinline__ void sgb_steady() {
 // moves the row sum out of the softmax phase, behind the PV MFMAs of the next matrix phase (unpack
 // the rounded weights by shift / mask, add: four plain VALU instructions per MFMA, which a lone
 // wave hides behind its MFMAs in an issue probe — in this kernel they cost 13 % more time);
-// -DSP_PREFILL_PRIO raises the wave priority during the matrix phases.
+// -DSP_PREFILL_PRIO raises the wave priority during the matrix phases; -DSP_PREFILL_QSCALED folds
+// scale * log2(e) into the resident Q operand and anchors the running max at 0 where the first
+// tile allows it, so that the common softmax pass is exp2, add and half a convert per score (2.5
+// VALU instructions instead of 3.5) — no change in time; -DSP_PREFILL_BARRIER_IN_SEQ puts the
+// second group's barrier before the last four MFMAs of its matrix phase, so that the first
+// group's operand reads after the barrier run behind them — no change in time either.
 #ifdef SP_PREFILL_PRIO
 #define SP_MATRIX_PHASE_BEGIN() __builtin_amdgcn_s_setprio(3)
 #define SP_MATRIX_PHASE_END() __builtin_amdgcn_s_setprio(0)
@@ -73,6 +78,16 @@ __device__ __forceinline__ void sgb_steady() {
 constexpr bool kAlwaysFullSoftmax = true;
 #else
 constexpr bool kAlwaysFullSoftmax = false;
+#endif
+#ifdef SP_PREFILL_BARRIER_IN_SEQ
+constexpr bool kBarrierInSeq = true;
+#else
+constexpr bool kBarrierInSeq = false;
+#endif
+#ifdef SP_PREFILL_QSCALED
+constexpr bool kScaledQSwitch = true;
+#else
+constexpr bool kScaledQSwitch = false;
 #endif
 
 struct PrefillArgs {
@@ -348,6 +363,33 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       qreg[s] = *reinterpret_cast<bf16x8 *>(&z);
     }
   }
+  // Rows with at most kPreciseKeys keys get hi + lo weights (see pv_residual below); the workgroups
+  // that hold such rows run their own copy of the tile loop.
+  constexpr int kPreciseKeys = 256;
+  const bool precise_wg = ctx + tok0 < kPreciseKeys;  // group-uniform
+  constexpr bool kScaledQ = kScaledQSwitch && !SPLIT && !PART;
+  if (kScaledQ && !precise_wg) {
+    // Fold scale * log2(e) into the resident Q operand: the scores then leave the MFMAs in the
+    // exponent's units and the softmax needs no multiply.  The product is rounded to bf16 again
+    // (relative 2^-9 per component, a perturbation of each score far below the rounding of the
+    // weights themselves).
+#pragma unroll
+    for (int s = 0; s < G::kDSteps; ++s) {
+      union {
+        bf16x8 v;
+        uint32_t w[4];
+        bf16x2 h[4];
+      } u;
+      u.v = qreg[s];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = __uint_as_float(u.w[i] << 16) * a.sl2e;
+        const float hi = __uint_as_float(u.w[i] & 0xffff0000u) * a.sl2e;
+        u.h[i] = __builtin_convertvector((f32x2){lo, hi}, bf16x2);
+      }
+      qreg[s] = u.v;
+    }
+  }
   const int wtok_first = tok0 + ((wc * 32) >> a.gshift);
   const int wtok_last = tok0 + (((wc + 1) * 32 - 1) >> a.gshift);
   const int wlim_min = wtok_last < q_len ? ctx + wtok_first + 1 : 1;
@@ -361,6 +403,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // all: its running max starts at a large finite value so that "all masked" gives weights
   // exp2(-inf) = 0 instead of exp2(-inf + inf).  Tile 0 always holds a visible key otherwise.
   float m_used = (SPLIT || PART) ? -1e30f : -INFINITY, l = 0.f, l2 = 0.f;  // row sum in two chains
+  bool m_zero = false;  // wave-uniform: every column's running max is the anchor 0 (scaled-Q form only)
   f32x16 sacc[KB];
   bf16x8 pop[KB][2];
 
@@ -536,7 +579,12 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op, qreg[s], sacc[b], 0, 0, 0);
     }
   };
-  auto mfma_seq = [&](auto I0c, auto I1c, auto stagec, auto ksc, auto vsc) __attribute__((always_inline)) {
+  // TAILB: the workgroup barrier sits inside the sequence, before its last PFD MFMAs.  All LDS
+  // reads of the sequence are done by then (their operands wait in registers), so the waves on
+  // the other side of the barrier may overwrite the slots, and their first operand reads run
+  // behind these trailing MFMAs instead of leaving the matrix pipe idle.
+  auto mfma_seq = [&](auto I0c, auto I1c, auto stagec, auto ksc, auto vsc, auto tailc) __attribute__((always_inline)) {
+    constexpr bool TAILB = decltype(tailc)::value;
     constexpr int I0 = decltype(I0c)::value, I1 = decltype(I1c)::value, N = I1 - I0;
     constexpr int KS = decltype(ksc)::value, VS = decltype(vsc)::value;  // K and V slots read
     constexpr bool STAGE = decltype(stagec)::value;  // emit this period's tile loads along the way
@@ -546,6 +594,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     for (int i = 0; i < PFD && i < N; ++i) ops[i] = load_op(I0 + i, KS, VS);
 #pragma unroll
     for (int i = 0; i < N; ++i) {
+      if (TAILB && i == N - PFD) {
+        sgb_prologue<0, N, I0, NPV, PFD>();
+        sgb_steady<0, N, I0, NPV, PFD, 0, N - PFD>();
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (i + PFD < N) ops[i + PFD] = load_op(I0 + i + PFD, KS, VS);
       do_mfma(I0 + i, ops[i]);
       if (STAGE && i % GAP == 0 && i / GAP * PER < NLD) {
@@ -558,24 +613,26 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     // sinks their adds out of the matrix phase into the softmax that follows
     if (I0 < NPV) asm volatile("" : "+v"(l), "+v"(l2));
 #endif
-    sgb_prologue<0, N, I0, NPV, PFD>();
+    if (!TAILB) {
+      sgb_prologue<0, N, I0, NPV, PFD>();
 #ifdef SP_PREFILL_SUM_IN_MATRIX_PHASE
-    sgb_steady<0, N, I0, NPV, PFD, 4 * RPM>();
+      sgb_steady<0, N, I0, NPV, PFD, 4 * RPM>();
 #else
-    sgb_steady<0, N, I0, NPV, PFD, 0>();
+      sgb_steady<0, N, I0, NPV, PFD, 0>();
 #endif
+    }
   };
   using slot0 = integral_constant<int, 0>;
   using slot1 = integral_constant<int, 1>;
   auto qk0 = [&]() __attribute__((always_inline)) {  // QK^T of a stream's first tile (K slot 0); its loads went out in the prologue
-    mfma_seq(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, false_type{}, slot0{}, slot0{});
+    mfma_seq(integral_constant<int, NPV>{}, integral_constant<int, NPV + NQK>{}, false_type{}, slot0{}, slot0{}, false_type{});
   };
   auto pv = [&](auto vsc) __attribute__((always_inline)) {  // PV of the tile in V slot vsc
-    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV>{}, false_type{}, slot0{}, vsc);
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV>{}, false_type{}, slot0{}, vsc, false_type{});
   };
-  auto pv_qk = [&](auto stagec, auto parc) __attribute__((always_inline)) {  // period i of parity parc: PV of tile i-1 (V slot 1 - par), QK^T of tile i (K slot par)
+  auto pv_qk = [&](auto stagec, auto parc, auto tailc) __attribute__((always_inline)) {  // period i of parity parc: PV of tile i-1 (V slot 1 - par), QK^T of tile i (K slot par)
     constexpr int PAR = decltype(parc)::value;
-    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, stagec, parc, integral_constant<int, 1 - PAR>{});
+    mfma_seq(integral_constant<int, 0>{}, integral_constant<int, NPV + NQK>{}, stagec, parc, integral_constant<int, 1 - PAR>{}, tailc);
   };
   // Softmax of tile t.  The common case (FIRST = false, and the tile's scores stay within 2^8 of
   // the running max) is one pass of 3.5 VALU instructions per score: weight = exp2(score * c -
@@ -588,7 +645,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // (Summing the rounded pairs with the bf16 dot-product instruction instead would be half the
   // additions, but measured it costs a third more cycles for the whole kernel: next to MFMAs that
   // instruction is far from full rate.)
-  auto softmax = [&](int t, auto firstc, bool keep_fp32) __attribute__((always_inline)) {
+  auto softmax = [&](int t, auto firstc, bool keep_fp32, auto qsc) __attribute__((always_inline)) {
+    constexpr bool QS = decltype(qsc)::value;  // scores arrive in the exponent's units (Q was prescaled)
     constexpr bool FIRST = decltype(firstc)::value;  // keep_fp32 (wave-uniform): take the full pass, the residual pass follows
     const int base = gtile(t) * KVT;
     if (base + KVT > wlim_min) {
@@ -602,8 +660,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     }
     float lsum = 0.f;
     bool full = FIRST || keep_fp32 || kAlwaysFullSoftmax;
+    const float sc = QS ? 1.0f : a.sl2e;
     if (!full) {
-      const float msc = m_used * a.sl2e;
+      const float msc = m_used * sc;
 #ifdef SP_PREFILL_SUM_IN_MATRIX_PHASE
       uint32_t pmax = 0;  // weights are >= 0, so their bit patterns order like their values (and NaN sorts above all)
 #pragma unroll
@@ -630,6 +689,27 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 #ifdef SP_PREFILL_SUM_MFMA
       f32x4 lacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #endif
+      if (QS && m_zero) {
+        // no running max to subtract: 2.5 VALU instructions per score
+#pragma unroll
+        for (int b = 0; b < KB; ++b)
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            union {
+              bf16x2 h[4];
+              bf16x8 v;
+            } u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float p0 = __builtin_amdgcn_exp2f(sacc[b][8 * ks + 2 * i]);
+              const float p1 = __builtin_amdgcn_exp2f(sacc[b][8 * ks + 2 * i + 1]);
+              u.h[i] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+              ls0 += p0;
+              ls1 += p1;
+            }
+            pop[b][ks] = u.v;
+          }
+      } else
 #pragma unroll
       for (int b = 0; b < KB; ++b)
 #pragma unroll
@@ -640,8 +720,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
           } u;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i], a.sl2e, -msc));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i + 1], a.sl2e, -msc));
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i], sc, -msc));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][8 * ks + 2 * i + 1], sc, -msc));
             u.h[i] = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
 #if defined(SP_PREFILL_SUM_DOT2)
             ls0 = __builtin_amdgcn_fdot2_f32_bf16(u.h[i], (bf16x2){(__bf16)1.0f, (__bf16)1.0f}, ls0, false);
@@ -672,7 +752,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       lsum = ls0 + ls1;
 #endif
       // NaN (a masked score against a running max that is still -inf) must take the full pass too
-      full = __builtin_amdgcn_ballot_w64(!(lsum <= 256.0f)) != 0;  // wave-uniform, rare
+      full = __builtin_amdgcn_ballot_w64(!(lsum <= (QS ? 0x1p40f : 256.0f))) != 0;  // wave-uniform, rare
 #endif
     }
     if (full) {
@@ -682,10 +762,14 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[b][r]);
       mx = fmaxf(mx, other_half(mx));
-      if (__builtin_amdgcn_ballot_w64(mx > m_used + a.tau) != 0) {  // wave-uniform
-        const float m_new = fmaxf(m_used, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * a.sl2e);
+      if (__builtin_amdgcn_ballot_w64(mx > m_used + (QS ? 8.0f : a.tau)) != 0) {  // wave-uniform
+        float m_new = fmaxf(m_used, mx);
+        // scaled-Q form: a first max within 2^+-32 anchors the column at 0, and while every column
+        // of the wave sits there the fast pass skips the subtraction
+        if (QS && FIRST && fabsf(mx) <= 32.0f) m_new = 0.f;
+        const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * sc);
         m_used = m_new;
+        if (QS) m_zero = __builtin_amdgcn_ballot_w64(m_used != 0.f) == 0;
         l *= alpha;
         l2 *= alpha;
 #pragma unroll
@@ -693,13 +777,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
       }
-      const float msc = m_used * a.sl2e;
+      const float msc = m_used * sc;
       lsum = 0.f;
 #pragma unroll
       for (int b = 0; b < KB; ++b) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          sacc[b][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][r], a.sl2e, -msc));
+          sacc[b][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][r], sc, -msc));
 #ifndef SP_PREFILL_SUM_IN_MATRIX_PHASE
           lsum += sacc[b][r];
 #endif
@@ -717,8 +801,6 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // kPreciseKeys.  The pass needs the fp32 weights (the softmax's full pass leaves them in sacc)
   // and V of that tile in LDS: it runs at the start of the following period, before QK^T
   // overwrites sacc.
-  constexpr int kPreciseKeys = 256;
-  const bool precise_wg = ctx + tok0 < kPreciseKeys;  // group-uniform
   auto precise = [&](int i) __attribute__((always_inline)) { return precise_wg && i >= 0 && gtile(i) * KVT < kPreciseKeys; };
   auto pv_residual = [&](auto vsc) __attribute__((always_inline)) {
 #pragma unroll
@@ -775,16 +857,16 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
     constexpr bool PREC = decltype(precc)::value;
     if (grp == 0) {  // always has Tl == P >= 1
       qk0();  // the loads of period 0 went out in the prologue
-      softmax(0, true_type{}, false);
+      softmax(0, true_type{}, false, integral_constant<bool, kScaledQ && !PREC>{});
       __syncthreads();
       auto period = [&](int t, auto parc) __attribute__((always_inline)) {
         constexpr int PAR = decltype(parc)::value;
         if (PREC && precise(t - 1)) pv_residual(integral_constant<int, 1 - PAR>{});  // V(t-1) became visible at the barrier
         issue_prep(t, parc);
         SP_MATRIX_PHASE_BEGIN();
-        pv_qk(true_type{}, parc);
+        pv_qk(true_type{}, parc, false_type{});
         SP_MATRIX_PHASE_END();
-        softmax(t, false_type{}, PREC && precise(t));
+        softmax(t, false_type{}, PREC && precise(t), integral_constant<bool, kScaledQ && !PREC>{});
         wait_loads();
         __syncthreads();
       };
@@ -805,15 +887,15 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       if (Tl > 0) qk0();
       __syncthreads();
       if (Tl > 0) {
-        softmax(0, true_type{}, false);
+        softmax(0, true_type{}, false, integral_constant<bool, kScaledQ && !PREC>{});
         auto period = [&](int t, auto parc) __attribute__((always_inline)) {
           constexpr int PAR = decltype(parc)::value;
           if (PREC && precise(t - 1)) pv_residual(integral_constant<int, 1 - PAR>{});
           SP_MATRIX_PHASE_BEGIN();
-          pv_qk(false_type{}, parc);
+          pv_qk(false_type{}, parc, integral_constant<bool, kBarrierInSeq>{});  // the period's barrier is inside
           SP_MATRIX_PHASE_END();
-          __syncthreads();
-          softmax(t, false_type{}, PREC && precise(t));
+          if (!kBarrierInSeq) __syncthreads();
+          softmax(t, false_type{}, PREC && precise(t), integral_constant<bool, kScaledQ && !PREC>{});
         };
         int t = 1;
         for (; t + 1 < Tl; t += 2) {
