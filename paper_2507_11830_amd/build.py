@@ -56,6 +56,51 @@ def _check_m0(src: str, asm: str) -> None:
                            + "\n".join(bad[:10]))
 
 
+def loop_spills(asm: str) -> dict:
+    """Scratch (register spill) instructions inside loops, per kernel of an assembly listing.
+    The prefill kernel sits at the register limit, and where the allocator puts its spill code
+    changes with unrelated edits; a reload on the tile loop's common path costs 5-20 % (it is
+    waited for right before the period's barrier).  Loop membership comes from the compiler's
+    own block comments ("in Loop: Header=...")."""
+    out, kern, inloop = {}, None, False
+    with open(asm) as f:
+        lines = f.read().split("\n")
+    i = 0
+    while i < len(lines):
+        line = lines[i]
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            kern, inloop = m.group(1), False
+            out[kern] = 0
+        elif line.startswith(".Lfunc_end"):
+            kern = None
+        elif kern and (line.startswith(".LBB") or line.strip().startswith("; %bb.")):
+            text, j = line, i + 1
+            while j < len(lines) and lines[j].strip().startswith(";") and not lines[j].strip().startswith("; %bb."):
+                text += lines[j]
+                j += 1
+            marked = "in Loop" in text or "Loop Header" in text
+            inloop = marked if line.startswith(".LBB") else (inloop or marked)  # fall-through blocks stay in their loop
+            i = j
+            continue
+        elif kern and inloop and "scratch_" in line.split(";")[0]:
+            out[kern] += 1
+        i += 1
+    return out
+
+
+def _check_loop_spills(src: str, asm: str) -> None:
+    """The one-workgroup-per-query-tile prefill kernels (the C5a path) must keep their loops free of
+    spill code; the split forms are allowed the few reloads of their rarely taken short-row copy."""
+    for kern, n in loop_spills(asm).items():
+        if "prefill_kernel" not in kern:
+            continue
+        main_form = re.search(r"ELb0ELb0E", kern) is not None
+        if n > (0 if main_form else 8):
+            raise RuntimeError(f"{os.path.basename(src)}: {n} spill instructions inside the loops of {kern}; "
+                               "the register allocation moved, look at the listing")
+
+
 def _compile(src: str, obj_dir: str = OBJ_DIR, extra_flags=()) -> str:
     base = os.path.basename(src).replace(".hip", "")
     obj = os.path.join(obj_dir, base + ".o")
@@ -72,6 +117,8 @@ def _compile(src: str, obj_dir: str = OBJ_DIR, extra_flags=()) -> str:
             raise RuntimeError(f"{os.path.basename(src)}: the compiler left no {asm}; the M0 check cannot run, "
                                "so the build is refused")
         _check_m0(src, asm)
+        if not os.environ.get("SP_HIPCC_EXTRA"):  # measurement builds may spill
+            _check_loop_spills(src, asm)
     return obj
 
 

@@ -222,3 +222,30 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "one GPU" in r.stderr
+
+
+def test_prefill_loops_hold_no_spill_code(built_lib):
+    """The build refuses a prefill kernel whose one-workgroup-per-query-tile form spills inside its
+    loops (a reload on the tile loop's common path costs 5-20 %); this checks the listing that
+    the build left behind, with the build's own scanner, and the scanner on a planted case."""
+    import glob
+    import tempfile
+
+    from paper_2507_11830_amd import build as b
+
+    planted = "\n".join(["_Zk:", ".LBB0_1:   ; in Loop: Header=BB0_1 Depth=1", "\tscratch_load_dword v1, off, off",
+                         "; %bb.2:", "\tscratch_store_dword off, v1, off", ".LBB0_3:", "\tscratch_load_dword v1, off, off",
+                         ".Lfunc_end0:"])
+    with tempfile.NamedTemporaryFile("w", suffix=".s", delete=False) as f:
+        f.write(planted)
+    try:
+        assert b.loop_spills(f.name) == {"_Zk": 2}
+    finally:
+        os.unlink(f.name)
+    listings = glob.glob(os.path.join(os.path.dirname(b.__file__), "_build", "attn_prefill-hip-amdgcn-amd-amdhsa-gfx950.s"))
+    if not listings:
+        pytest.skip("no assembly listing from this build")
+    counts = {k: v for k, v in b.loop_spills(listings[0]).items() if "prefill_kernel" in k}
+    assert len(counts) == 6
+    for kern, n in counts.items():
+        assert n <= (0 if "ELb0ELb0E" in kern else 8), (kern, n)
