@@ -101,7 +101,7 @@ def _check_loop_spills(src: str, asm: str) -> None:
                                "the register allocation moved, look at the listing")
 
 
-def _compile(src: str, obj_dir: str = OBJ_DIR, extra_flags=()) -> str:
+def _compile(src: str, obj_dir: str = OBJ_DIR, extra_flags=(), product: bool = True) -> str:
     base = os.path.basename(src).replace(".hip", "")
     obj = os.path.join(obj_dir, base + ".o")
     with open(src) as f:
@@ -117,7 +117,7 @@ def _compile(src: str, obj_dir: str = OBJ_DIR, extra_flags=()) -> str:
             raise RuntimeError(f"{os.path.basename(src)}: the compiler left no {asm}; the M0 check cannot run, "
                                "so the build is refused")
         _check_m0(src, asm)
-        if not os.environ.get("SP_HIPCC_EXTRA"):  # measurement builds may spill
+        if product and not os.environ.get("SP_HIPCC_EXTRA"):  # measurement and sanitizer builds may spill
             _check_loop_spills(src, asm)
     return obj
 
@@ -152,7 +152,7 @@ def build_sanitized(verbose: bool = False) -> str:
     os.makedirs(out_dir, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(lambda s_: _compile(s_, out_dir, SAN_FLAGS), srcs))
+        objs = list(ex.map(lambda s_: _compile(s_, out_dir, SAN_FLAGS, product=False), srcs))
     _link(objs, SAN_LIB, ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"])
     if verbose:
         print("built", SAN_LIB)
