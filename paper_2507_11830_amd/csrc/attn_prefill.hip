@@ -15,11 +15,13 @@
 // traffic is ~1/(8*columns) of that in bytes and is served mostly from L2.  Next to the matrix
 // pipe the kernel keeps the VALU (softmax: 3.5 instructions per score, the exponential at half
 // rate) and LDS (every MFMA takes one 1 KiB operand from it) busy at the same time.  Measured on
-// a 32 k-token prefill, the number of VALU instructions decides the cycle count (one more
-// instruction per score costs a quarter more cycles), so the softmax is a single pass without a
-// tile max and the matrix phases carry no address arithmetic; the matrix pipe is then busy in
-// about 85 % of the cycles a CU is busy, and what limits the kernel beyond that is the clock the
-// chip grants under this load.
+// a 32 k-token prefill, a tile max in every tile (a reduction plus a cross-lane step in front of
+// every exponential) costs a quarter more cycles, and so do VALU instructions between the MFMAs
+// of a matrix phase, while one plain instruction per score more or less in the softmax phase
+// changes nothing at head_dim 128: so the softmax is a single pass without a tile max and the
+// matrix phases carry no address arithmetic.  The matrix pipe is then busy in about 85 % of the
+// cycles a CU is busy, and what limits the kernel beyond that is the clock the chip grants under
+// this load (it is power-limited from the first tile on).
 #include <type_traits>
 
 #include "attn_tile.h"
