@@ -66,8 +66,8 @@ __device__ __forceinline__ void sgb_steady() {  // MFMAs [I, NE) of a sequence o
 // -DSP_PREFILL_PRIO raises the wave priority during the matrix phases; -DSP_PREFILL_QSCALED folds
 // scale * log2(e) into the resident Q operand and anchors the running max at 0 where the first
 // tile allows it, so that the common softmax pass is exp2, add and half a convert per score (2.5
-// VALU instructions instead of 3.5), also at head_dim 128, where it changes nothing in time
-// (head_dim 64 always runs that form); -DSP_PREFILL_BARRIER_IN_SEQ puts the
+// VALU instructions instead of 3.5) — no change in time at head_dim 128, 9 % faster at head_dim
+// 64, at the price of a score error that grows with the score; -DSP_PREFILL_BARRIER_IN_SEQ puts the
 // second group's barrier before the last four MFMAs of its matrix phase, so that the first
 // group's operand reads after the barrier run behind them — no change in time either.
 #ifdef SP_PREFILL_PRIO
@@ -370,11 +370,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   // that hold such rows run their own copy of the tile loop.
   constexpr int kPreciseKeys = 256;
   const bool precise_wg = ctx + tok0 < kPreciseKeys;  // group-uniform
-  // head_dim 64 halves the MFMAs per score, which leaves the softmax phase longer than the other
-  // wave's matrix phase: there the scaled-Q form (2.5 instead of 3.5 VALU instructions per score)
-  // is 9 % faster and is what the one-workgroup-per-query-tile kernel uses.  At head_dim 128 the
-  // softmax is hidden either way and Q stays as given.
-  constexpr bool kScaledQ = (kScaledQSwitch || D == 64) && !SPLIT && !PART;
+  // The scaled-Q form (measurement switch): 2.5 instead of 3.5 VALU instructions per score.  At
+  // head_dim 64, where halving the MFMAs per score leaves the softmax phase longer than the other
+  // wave's matrix phase, it is 9 % faster; at head_dim 128 it changes nothing.  It is not the
+  // product form at either: Q * scale * log2(e) is rounded to bf16 again, so the error of a score
+  // grows with the score (relative 2^-9 per term), which is invisible on unit-variance inputs and
+  // several per cent of a weight once scores reach the tens — the product keeps Q's products exact.
+  constexpr bool kScaledQ = kScaledQSwitch && !SPLIT && !PART;
   if (kScaledQ && !precise_wg) {
     // Fold scale * log2(e) into the resident Q operand: the scores then leave the MFMAs in the
     // exponent's units and the softmax needs no multiply.  The product is rounded to bf16 again
