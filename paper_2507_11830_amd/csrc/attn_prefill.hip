@@ -70,6 +70,21 @@ __device__ __forceinline__ void sgb_steady() {  // MFMAs [I, NE) of a sequence o
 // 64, at the price of a score error that grows with the score; -DSP_PREFILL_BARRIER_IN_SEQ puts the
 // second group's barrier before the last four MFMAs of its matrix phase, so that the first
 // group's operand reads after the barrier run behind them — no change in time either.
+// -DSP_PREFILL_TRACE makes launches that do not use the workspace otherwise (no key-range pieces,
+// no routed short sequences) write a timeline into it: per workgroup the 100 MHz wall clock at its
+// start, after the prologue's barrier, at the end of either wave group's tile loop and at its end,
+// its tile count and the CU it ran on, and for every eighth tile period of the first group the
+// wall clock and the shader clock (paper_2507_11830_amd/trace_prefill.py reads it).
+#ifdef SP_PREFILL_TRACE
+constexpr int kTraceWgs = 8192, kTraceRec = 8, kTracePer = 64;  // workgroups covered, longs per record, period stamps
+constexpr size_t kTraceBytes = (size_t)kTraceWgs * (kTraceRec + 2 * kTracePer) * sizeof(long);
+#define SP_TRACE_STAMP(slot, tid)                                                  \
+  do {                                                                             \
+    if (trace_rec && threadIdx.x == (tid)) trace_rec[slot] = (long)wall_clock64(); \
+  } while (0)
+#else
+#define SP_TRACE_STAMP(slot, tid)
+#endif
 #ifdef SP_PREFILL_PRIO
 #define SP_MATRIX_PHASE_BEGIN() __builtin_amdgcn_s_setprio(3)
 #define SP_MATRIX_PHASE_END() __builtin_amdgcn_s_setprio(0)
@@ -284,6 +299,12 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   static_assert((TBYTES & (TBYTES - 1)) == 0, "slot toggling flips one address bit");
   extern __shared__ __align__(16) char smem_raw[];
   lds_char *smem = (lds_char *)smem_raw;
+#ifdef SP_PREFILL_TRACE
+  const unsigned trace_wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  long *trace_rec = !PART && a.part_o && trace_wg < (unsigned)kTraceWgs ? (long *)a.part_o + (size_t)trace_wg * kTraceRec : nullptr;
+  long *trace_per = trace_rec ? (long *)a.part_o + (size_t)kTraceWgs * kTraceRec + (size_t)trace_wg * kTracePer : nullptr;
+  SP_TRACE_STAMP(0, 0);
+#endif
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps branches on it scalar
@@ -847,6 +868,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   }
   wait_loads();
   __syncthreads();
+  SP_TRACE_STAMP(1, 0);
 
   // One barrier per key tile.  Inside a tile period the two groups run the same two phases in
   // OPPOSITE order: the first group multiplies (PV of tile t-1, QK^T of tile t) and then
@@ -870,6 +892,12 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
       __syncthreads();
       auto period = [&](int t, auto parc) __attribute__((always_inline)) {
         constexpr int PAR = decltype(parc)::value;
+#ifdef SP_PREFILL_TRACE
+        if (trace_per && threadIdx.x == 0 && (t & 7) == 0 && t < 8 * kTracePer) {
+          trace_per[t >> 3] = (long)wall_clock64();
+          trace_per[(size_t)kTraceWgs * kTracePer + (t >> 3)] = (long)clock64();
+        }
+#endif
         if (PREC && precise(t - 1)) pv_residual(integral_constant<int, 1 - PAR>{});  // V(t-1) became visible at the barrier
         issue_prep(t, parc);
         SP_MATRIX_PHASE_BEGIN();
@@ -925,6 +953,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
   };
   if (precise_wg) tile_loop(true_type{});
   else tile_loop(false_type{});
+  SP_TRACE_STAMP(2, 0);
+  SP_TRACE_STAMP(3, 256);
 
   if (SPLIT) {
     // ---- merge the second group's running state into the first group's (same columns, same
@@ -982,6 +1012,15 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel(PrefillArgs a) {
         store4_bf16(dst + (32 * db + 8 * r4 + 4 * half) * 2, o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv,
                     o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv);
   }
+#ifdef SP_PREFILL_TRACE
+  SP_TRACE_STAMP(4, 0);
+  if (trace_rec && threadIdx.x == 0) {
+    trace_rec[5] = T_all;
+    // HW_ID (wave, SIMD, CU, shader array, shader engine) and XCC_ID of the wave
+    trace_rec[6] = (long)__builtin_amdgcn_s_getreg((31 << 11) | 4) | ((long)__builtin_amdgcn_s_getreg((3 << 11) | 20) << 32);
+    trace_rec[7] = ((long)seq << 32) | (unsigned)tile;
+  }
+#endif
 }
 
 // Launch-shape overrides of the calling thread (sp_debug_set_tuning); 0 = built-in heuristic.
@@ -1181,6 +1220,9 @@ int launch_prefill(const sp_cache_desc &c, const void *q, void *out, const int32
   while (a.rank_shift < 24 && (max_kv_len >> a.rank_shift) > 63) ++a.rank_shift;
   a.part_o = (float *)workspace;
   a.part_ml = a.part_o + (size_t)rows * kvs * c.head_dim;
+#ifdef SP_PREFILL_TRACE
+  if (kvs == 1 && (a.route_cap > 0 || workspace_bytes < kTraceBytes)) a.part_o = nullptr;  // no room for the timeline
+#endif
 
   const bool split = small_grid || kvs > 1;
   int rc = c.head_dim == 128 ? launch_prefill_d<128>(a, split, batch, max_q_len, stream)
